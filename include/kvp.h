@@ -1,0 +1,164 @@
+/*
+ * kvp.h -- C ABI of libkvp: the KV-cache compress / decompress hot path of
+ * EvicPress (arxiv 2512.14946) on one MI355X (gfx950).
+ *
+ * The paper's system compresses the KV cache of a context "into multiple
+ * versions" with different methods and ratios, scores every version, and on a
+ * cache hit loads the chosen version back into the serving engine's paged GPU
+ * memory (System design: profiler module, utility function; Implementation:
+ * lookup / retrieve / store / manage).  This library is the data-parallel part
+ * of that: quantize, dequantize into pages, score tokens, select a keep-set,
+ * and evaluate a quality-loss proxy for every candidate configuration.
+ *
+ * Conventions for every call
+ *   - All tensor pointers are DEVICE pointers unless a comment says "host".
+ *     The structs themselves and kvp_config arrays are read on the HOST.
+ *   - The caller owns every buffer.  The library never allocates, frees or
+ *     keeps a pointer after the call returns.  Scratch memory comes from the
+ *     caller as (ws, ws_bytes); the size needed is returned by the matching
+ *     kvp_*_workspace_bytes call.
+ *   - Calls validate their arguments on the host, enqueue kernels on `stream`
+ *     (a hipStream_t passed as void*; NULL = the default stream) and return
+ *     without synchronizing.  A call that fails validation enqueues nothing.
+ *   - Device pointers must be 16-byte aligned and strides must keep every row
+ *     of D elements 16-byte aligned.  head_dim D must be 128.
+ *   - Results are deterministic: the same inputs give the same bytes.
+ *   - Return value: KVP_OK or a negative KVP_ERR_* code; kvp_strerror() names it.
+ */
+#ifndef KVP_H_
+#define KVP_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+  KVP_OK = 0,
+  KVP_ERR_NULL = -1,        /* a required pointer is NULL */
+  KVP_ERR_ALIGN = -2,       /* a pointer or stride breaks the 16-byte row alignment */
+  KVP_ERR_SHAPE = -3,       /* sizes inconsistent (k > T, W > T, Hq % Hkv != 0, D % group != 0, ...) */
+  KVP_ERR_UNSUPPORTED = -4, /* bits not in {8,4,2} (16 allowed in kvp_config), group not in {32,64,128}, D != 128 */
+  KVP_ERR_WORKSPACE = -5,   /* ws is NULL or ws_bytes is smaller than kvp_*_workspace_bytes() */
+  KVP_ERR_LAUNCH = -6       /* the HIP runtime refused a launch */
+};
+
+/* Strided bf16 tensor [L][T][H][D], innermost D contiguous; strides in elements. */
+typedef struct {
+  const void* ptr; /* device, bf16 */
+  int64_t L, T, H, D;
+  int64_t stride_l, stride_t, stride_h;
+} kvp_view;
+
+/* Paged bf16 plane (K or V) in the serving engine's page pool (Background:
+ * PagedAttention's page-like blocks; Implementation: retrieve puts the KV
+ * cache "into the paged GPU memory").  Token t of layer l lives at
+ * pool[l][block_table[t / bs]][t % bs][h][:].  One block table per context,
+ * shared by all layers.  Entries must lie in [0, num_blocks). */
+typedef struct {
+  void* pool;                 /* device, bf16 [L][num_blocks][bs][H][D], layers stride_l elements apart */
+  const int32_t* block_table; /* device, int32 [ceil(T / bs)] */
+  int64_t L, num_blocks, bs, H, D, T;
+  int64_t stride_l;
+} kvp_paged;
+
+/* Compressed plane: packed codes and one fp32 scale per group.  Slot s of head
+ * h holds one token's D channels: D*bits/8 bytes, channel order, fields packed
+ * little-endian inside a byte, two's complement truncated to `bits`.  Slots
+ * T <= s < Tp are padding (zero codes, zero scales) so that the plane splits
+ * into whole pages of the compressed store; Tp >= T. */
+typedef struct {
+  uint8_t* codes; /* device [L][Tp][H][D*bits/8] */
+  float* scales;  /* device [L][Tp][H][D/group] */
+  int32_t bits, group;
+  int64_t L, T, Tp, H, D;
+} kvp_qplane;
+
+/* One candidate configuration of the utility table: quantization (bits = 16
+ * means none; group is then ignored) and the number of tokens kept
+ * (keep_k = T means no token dropping). */
+typedef struct {
+  int32_t bits, group;
+  int64_t keep_k;
+} kvp_config;
+
+/* Group-wise symmetric quantization (Background, "KV cache compression":
+ * quantization "reduces the bit-width representation of KV entries"; Related
+ * work: uniform quantization; Limitations: pool "that combines both token
+ * dropping and quantization").  For every group of `group` consecutive channels
+ * of one token's head vector:
+ *     scale = max|x| / qmax   (qmax = 2^(bits-1) - 1; IEEE binary32 division)
+ *     code  = clamp(rint(x / scale), -qmax, qmax)   (binary32 division,
+ *             round-half-to-even; code 0 when scale == 0)
+ * Exactly one of `src` (strided view) and `src_paged` is non-NULL.  With
+ * `keep_idx` (device int32 [L][H][k], ascending, values in [0, T)) slot i of
+ * head h takes source token keep_idx[l][h][i] and dst->T must equal k;
+ * otherwise slot i is token i, k is ignored and dst->T must equal the source
+ * T.  Writes dst->codes and dst->scales in full, padding slots included. */
+int32_t kvp_quantize(const kvp_view* src, const kvp_paged* src_paged, const int32_t* keep_idx, int64_t k,
+                     const kvp_qplane* dst, void* stream);
+
+/* Inverse direction, into the paged pool (Background: quantization methods
+ * "have a decompression overhead"; Implementation: retrieve).  For t < src->T:
+ *     pool[l][block_table[t/bs]][t%bs][h][c] = bf16_rne((float)code * scale)
+ * (one binary32 multiply, then round-to-nearest-even to bf16).  Page slots at
+ * or beyond T and blocks the table does not name are not written.  dst->T
+ * must equal src->T; L, H, D must match. */
+int32_t kvp_dequantize_paged(const kvp_qplane* src, const kvp_paged* dst, void* stream);
+
+/* Attention-score token importance (Evaluation, Baselines: snapkv "computes
+ * the cross attention between tokens near the query and the earlier
+ * contexts").  q_win is [L][W][Hq][D]: the queries of the last W positions
+ * (T-W .. T-1) of the context; k is [L][T][Hkv][D]; G = Hq / Hkv query heads
+ * share kv head h (heads h*G .. h*G+G-1).  For each (l, h):
+ *     scores[l][h][t] = sum over the G*W window rows of softmax_t(q.k / sqrt(D))
+ * with keys after a row's own position masked when `causal`, and positions
+ * t >= T-W set to +inf when `force_window` (window tokens are always kept).
+ * bf16 inputs, fp32 accumulation.  scores is device fp32 [L][Hkv][T]. */
+int32_t kvp_score_tokens(const kvp_view* q_win, const kvp_view* k, int32_t causal, int32_t force_window,
+                         float* scores, void* ws, size_t ws_bytes, void* stream);
+size_t kvp_score_workspace_bytes(int64_t L, int64_t Hkv, int64_t Hq, int64_t W, int64_t T);
+
+/* Per-row top-k keep-set (Evaluation, Baselines: tokens "with low
+ * cross-attention scores" are dropped; IMPRESS keeps the top X%).  For each
+ * of n_rows rows of T fp32 scores (row_stride floats apart): the indices of the
+ * k largest, equal scores resolved toward the lowest index, written ascending
+ * to idx_out [n_rows][k] (device int32).  NaN scores are out of contract.
+ * 0 <= k <= T; T < 2^31. */
+int32_t kvp_select_topk(const float* scores, int64_t n_rows, int64_t T, int64_t row_stride, int64_t k,
+                        int32_t* idx_out, void* ws, size_t ws_bytes, void* stream);
+size_t kvp_select_workspace_bytes(int64_t n_rows, int64_t T, int64_t k);
+
+/* Quality-loss proxy for every candidate configuration of ONE context
+ * (System design, profiler module: the KV cache is compressed "with different
+ * methods and ratios" and every version is scored; utility function: the
+ * quality term).  For config c = (bits, group, keep_k):
+ *     O_full = softmax(Q K^T / sqrt(D)) V          (causal, the W window rows)
+ *     O_c    = the same with K, V replaced by dequantize(quantize(.)) at
+ *              (bits, group) and the keys restricted to the top-keep_k keep-set
+ *              of kvp_score_tokens(causal=1, force_window=1) on the unquantized K
+ *     loss[c] = sqrt( sum (O_c - O_full)^2 / sum O_full^2 )
+ * sums over layers, query heads, window rows and channels.  cfgs is a HOST
+ * array; loss is device fp32 [n_cfgs]; partial is NULL or device fp32
+ * [L][n_cfgs][2] = (numerator, denominator) per layer. */
+int32_t kvp_eval_configs(const kvp_view* q_win, const kvp_view* k, const kvp_view* v, const kvp_config* cfgs,
+                         int32_t n_cfgs, float* loss, float* partial, void* ws, size_t ws_bytes, void* stream);
+size_t kvp_eval_workspace_bytes(int64_t L, int64_t Hkv, int64_t Hq, int64_t W, int64_t T, int32_t n_cfgs);
+
+/* Host helper: tokens kept at a keep-ratio = ceil(ratio * T) in double, clamped to [1, T]. */
+int64_t kvp_keep_count(double ratio, int64_t T);
+
+/* Plain device-to-device copy kernel (nbytes a multiple of 16, both pointers
+ * 16-byte aligned).  Not part of the method: it is the yardstick the benchmark
+ * and the hardware-counter calibration compare the streaming kernels with. */
+int32_t kvp_copy_bytes(void* dst, const void* src, size_t nbytes, void* stream);
+
+const char* kvp_strerror(int32_t code);
+uint32_t kvp_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* KVP_H_ */

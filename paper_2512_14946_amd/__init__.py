@@ -1,0 +1,12 @@
+"""MI355X-native KV-cache compress / decompress hot path (after EvicPress, arxiv 2512.14946).
+
+The work is done by libkvp.so (hand-written HIP for gfx950, C ABI in include/kvp.h); this
+package only marshals torch tensors into that ABI.  There is no CPU fallback: if the library is
+not built, importing the binding raises.
+"""
+from .kvp import (  # noqa: F401
+    KVPError, PagedKV, QPlane, alloc_paged, alloc_qplane, kvp_copy_bytes, kvp_dequantize_paged,
+    kvp_eval_configs, kvp_eval_workspace_bytes, kvp_keep_count, kvp_quantize, kvp_score_tokens,
+    kvp_score_workspace_bytes, kvp_select_topk, kvp_select_workspace_bytes, kvp_strerror, kvp_version,
+    library_path,
+)

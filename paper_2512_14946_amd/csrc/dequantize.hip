@@ -1,0 +1,201 @@
+// kvp_dequantize_paged: packed int8/int4/int2 codes x fp32 group scales -> bf16 rows scattered into
+// the serving engine's page pool (the decompression step the paper's Background attributes to
+// quantization methods, landing in the paged GPU memory that retrieve() fills).
+//
+// Mapping.  One 256-thread block restores one page of one layer: bs tokens x H heads = bs*H rows
+// that are contiguous both in the compressed plane ([Tp][H][...], tokens t0 .. t0+bs-1) and in the
+// destination page, so a block reads one contiguous run of codes and scales and writes one
+// contiguous 32 KiB run (H = 8) with 128-bit stores; the block-table entry is read once per block.
+// A lane owns 8 consecutive channels of a row: it loads 8 / 4 / 2 bytes of codes and its group's
+// scale, and stores 16 bytes.  y = (float)code * scale is one binary32 multiply, rounded to bf16
+// (nearest even) on the integer pattern, so the output is bit-identical to the definition.
+
+#include "kvp_common.h"
+
+namespace kvp {
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kRowsPerStep = kThreads / kLanesPerRow;  // 16
+constexpr int kUnroll = 4;
+
+struct DequantArgs {
+  const uint8_t* codes;
+  const float* scales;
+  uint16_t* pool;
+  const int32_t* block_table;
+  int64_t pool_stride_l;   // elements
+  int64_t Tp;
+  uint32_t T, H, bs, num_blocks;
+};
+
+template <int BITS>
+__device__ __forceinline__ uint2 load_codes(const uint8_t* row_codes, int lane_in_row);
+template <>
+__device__ __forceinline__ uint2 load_codes<8>(const uint8_t* row_codes, int lane_in_row) {
+  return *reinterpret_cast<const uint2*>(row_codes + lane_in_row * 8);
+}
+template <>
+__device__ __forceinline__ uint2 load_codes<4>(const uint8_t* row_codes, int lane_in_row) {
+  return make_uint2(*reinterpret_cast<const uint32_t*>(row_codes + lane_in_row * 4), 0);
+}
+template <>
+__device__ __forceinline__ uint2 load_codes<2>(const uint8_t* row_codes, int lane_in_row) {
+  return make_uint2(*reinterpret_cast<const uint16_t*>(row_codes + lane_in_row * 2), 0);
+}
+
+// signed field i (of 8) of a lane's packed codes
+template <int BITS>
+__device__ __forceinline__ int field(const uint2 c, int i) {
+  if constexpr (BITS == 8) {
+    const uint32_t w = i < 4 ? c.x : c.y;
+    return __builtin_amdgcn_sbfe(static_cast<int>(w), 8 * (i & 3), 8);
+  } else {
+    return __builtin_amdgcn_sbfe(static_cast<int>(c.x), BITS * i, BITS);
+  }
+}
+
+template <int BITS, int GROUP>
+__global__ __launch_bounds__(kThreads) void dequantize_paged_kernel(const DequantArgs a) {
+  constexpr int CB = kHeadDim * BITS / 8;
+  constexpr int NS = kHeadDim / GROUP;
+  constexpr int LANES_PER_GROUP = GROUP / 8;
+  const int lane_in_row = threadIdx.x & (kLanesPerRow - 1);
+  const uint32_t row_in_step = threadIdx.x / kLanesPerRow;
+  const uint32_t page = blockIdx.x;
+  const uint32_t l = blockIdx.y;
+  const uint32_t t0 = page * a.bs;
+  const uint32_t tokens = min(a.bs, a.T - t0);
+  const uint32_t rows = tokens * a.H;  // rows of this page that hold tokens < T
+  // an out-of-contract table entry is clamped so that it cannot fault the GPU
+  const int64_t blk = min(static_cast<uint32_t>(a.block_table[page]), a.num_blocks - 1);
+  const int64_t src_row0 = (static_cast<int64_t>(l) * a.Tp + t0) * a.H;
+  const uint8_t* codes = a.codes + src_row0 * CB;
+  const float* scales = a.scales + src_row0 * NS;
+  uint16_t* dst = a.pool + static_cast<int64_t>(l) * a.pool_stride_l + blk * a.bs * a.H * kHeadDim;
+
+  for (uint32_t r0 = row_in_step; r0 < rows; r0 += kRowsPerStep * kUnroll) {
+    uint2 c[kUnroll];
+    float s[kUnroll];
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) {
+      const uint32_t r = r0 + u * kRowsPerStep;
+      c[u] = make_uint2(0, 0);
+      s[u] = 0.0f;
+      if (r < rows) {
+        c[u] = load_codes<BITS>(codes + static_cast<int64_t>(r) * CB, lane_in_row);
+        s[u] = scales[static_cast<int64_t>(r) * NS + lane_in_row / LANES_PER_GROUP];
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) {
+      const uint32_t r = r0 + u * kRowsPerStep;
+      if (r >= rows) continue;
+      uint32_t w[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const float lo = static_cast<float>(field<BITS>(c[u], 2 * i)) * s[u];
+        const float hi = static_cast<float>(field<BITS>(c[u], 2 * i + 1)) * s[u];
+        w[i] = pack_bf16x2(lo, hi);
+      }
+      *reinterpret_cast<uint4*>(dst + static_cast<int64_t>(r) * kHeadDim + lane_in_row * 8) =
+          make_uint4(w[0], w[1], w[2], w[3]);
+    }
+  }
+}
+
+template <int BITS>
+void launch_group(int group, dim3 grid, hipStream_t st, const DequantArgs& a) {
+  switch (group) {
+    case 32: dequantize_paged_kernel<BITS, 32><<<grid, kThreads, 0, st>>>(a); break;
+    case 64: dequantize_paged_kernel<BITS, 64><<<grid, kThreads, 0, st>>>(a); break;
+    default: dequantize_paged_kernel<BITS, 128><<<grid, kThreads, 0, st>>>(a); break;
+  }
+}
+
+__global__ __launch_bounds__(256) void copy_kernel(uint4* __restrict__ dst, const uint4* __restrict__ src, size_t n16) {
+  // 4 x 16 bytes per thread, block-contiguous
+  const size_t base = (static_cast<size_t>(blockIdx.x) * 256 * 4) + threadIdx.x;
+  uint4 v[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const size_t idx = base + static_cast<size_t>(i) * 256;
+    if (idx < n16) v[i] = src[idx];
+  }
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const size_t idx = base + static_cast<size_t>(i) * 256;
+    if (idx < n16) dst[idx] = v[i];
+  }
+}
+
+}  // namespace
+}  // namespace kvp
+
+extern "C" int32_t kvp_dequantize_paged(const kvp_qplane* src, const kvp_paged* dst, void* stream) {
+  using namespace kvp;
+  int32_t rc = check_qplane(src);
+  if (rc != KVP_OK) return rc;
+  rc = check_paged(dst);
+  if (rc != KVP_OK) return rc;
+  if (src->L != dst->L || src->H != dst->H || src->T != dst->T) return KVP_ERR_SHAPE;
+  if (dst->T >= (1ll << 31) || dst->bs * dst->H >= (1ll << 31) || dst->num_blocks >= (1ll << 31) || dst->L > 65535)
+    return KVP_ERR_SHAPE;
+  DequantArgs a{};
+  a.codes = src->codes;
+  a.scales = src->scales;
+  a.pool = static_cast<uint16_t*>(dst->pool);
+  a.block_table = dst->block_table;
+  a.pool_stride_l = dst->stride_l;
+  a.Tp = src->Tp;
+  a.T = static_cast<uint32_t>(dst->T);
+  a.H = static_cast<uint32_t>(dst->H);
+  a.bs = static_cast<uint32_t>(dst->bs);
+  a.num_blocks = static_cast<uint32_t>(dst->num_blocks);
+  const dim3 grid(static_cast<unsigned>(ceil_div(dst->T, dst->bs)), static_cast<unsigned>(dst->L));
+  const hipStream_t st = as_stream(stream);
+  switch (src->bits) {
+    case 8: launch_group<8>(src->group, grid, st, a); break;
+    case 4: launch_group<4>(src->group, grid, st, a); break;
+    default: launch_group<2>(src->group, grid, st, a); break;
+  }
+  return launch_status();
+}
+
+extern "C" int32_t kvp_copy_bytes(void* dst, const void* src, size_t nbytes, void* stream) {
+  using namespace kvp;
+  if (!dst || !src) return KVP_ERR_NULL;
+  if (!aligned16(dst) || !aligned16(src) || nbytes % 16) return KVP_ERR_ALIGN;
+  if (nbytes == 0) return KVP_OK;
+  const size_t n16 = nbytes / 16;
+  const size_t blocks = (n16 + 1023) / 1024;
+  if (blocks >= (1ull << 31)) return KVP_ERR_SHAPE;
+  copy_kernel<<<dim3(static_cast<unsigned>(blocks)), 256, 0, as_stream(stream)>>>(static_cast<uint4*>(dst),
+                                                                                   static_cast<const uint4*>(src), n16);
+  return launch_status();
+}
+
+extern "C" int64_t kvp_keep_count(double ratio, int64_t T) {
+  // ceil(ratio * T) evaluated in double, clamped to [1, T]
+  const double x = ratio * static_cast<double>(T);
+  int64_t k = static_cast<int64_t>(x);
+  if (static_cast<double>(k) < x) ++k;
+  if (k < 1) k = 1;
+  if (k > T) k = T;
+  return k;
+}
+
+extern "C" const char* kvp_strerror(int32_t code) {
+  switch (code) {
+    case KVP_OK: return "ok";
+    case KVP_ERR_NULL: return "a required pointer is NULL";
+    case KVP_ERR_ALIGN: return "pointer or stride breaks the 16-byte row alignment";
+    case KVP_ERR_SHAPE: return "inconsistent sizes";
+    case KVP_ERR_UNSUPPORTED: return "unsupported bits / group / head_dim";
+    case KVP_ERR_WORKSPACE: return "workspace missing or too small";
+    case KVP_ERR_LAUNCH: return "HIP launch failed";
+    default: return "unknown kvp error code";
+  }
+}
+
+extern "C" uint32_t kvp_version(void) { return 0x00010000u; }

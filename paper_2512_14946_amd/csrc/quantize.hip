@@ -1,0 +1,291 @@
+// kvp_quantize: group-wise symmetric quantization of bf16 K/V rows to int8/int4/int2 codes with
+// one fp32 scale per group (the quantization category of the paper's Background section,
+// "KV cache compression"; the formula is this library's stated reading, see include/kvp.h).
+//
+// Mapping.  A row (one token of one head, 128 bf16 = 256 B) is read by 16 adjacent lanes with one
+// 128-bit load each; a lane owns 8 consecutive channels.  A group of 128 / 64 / 32 channels is
+// 16 / 8 / 4 adjacent lanes of one DPP row, so the group abs-max is 4 / 3 / 2 cross-lane max steps
+// in registers.  A 256-thread block covers kRowsPerBlock consecutive rows of one layer; all loads of
+// a thread are issued before any arithmetic so that several KiB per wave are in flight.
+//
+// Bit-exact codes without one full IEEE division per element.  The defined result is
+// q = rint(fl32(x / scale)).  The kernel forms y0 = x * rcp(scale) (relative error far below
+// 2^-21), q0 = rint(y0), and accepts q0 whenever y0 is further than kTieMargin from the nearest
+// half-integer: the correctly rounded quotient then lies in the same rounding interval.  Elements
+// that are close to a half-integer are resolved exactly: if fma(-h, scale, x) == 0 the quotient IS
+// the half-integer h (common with bf16 inputs) and rounds to the even neighbour; otherwise the
+// element takes the full IEEE division.  Both slow steps sit behind wave-uniform branches.  For
+// int2 (codes -1, 0, +1, scale = amax) the code is +-1 exactly when 2|x| > amax, which needs no
+// division at all: x / amax is a ratio of two 8-bit significands and cannot round across 1/2.
+
+#include "kvp_common.h"
+
+namespace kvp {
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kRowsPerStep = kThreads / kLanesPerRow;  // 16 rows per load step
+constexpr int kSteps = 4;
+constexpr int kRowsPerBlock = kRowsPerStep * kSteps;   // 64 rows = 16 KiB of bf16 per block
+
+enum SrcMode { kLinear = 0, kStrided = 1, kPaged = 2 };
+
+struct QuantArgs {
+  const uint16_t* src;         // view base or page pool
+  int64_t stride_l, stride_t, stride_h;  // elements (view); stride_l also for the pool
+  const int32_t* block_table;  // paged source only
+  const int32_t* keep_idx;     // [L][H][k] or null
+  int64_t k;                   // row length of keep_idx
+  uint32_t n_slots;            // valid slots per layer (T, or k when gathered)
+  uint32_t T;                  // source tokens per layer
+  uint32_t num_blocks;         // paged source only
+  uint32_t rows_per_layer;     // Tp * H
+  uint32_t H, bs;
+  FastDiv div_h, div_bs;
+  uint8_t* codes;
+  float* scales;
+};
+
+template <int CTRL>
+__device__ __forceinline__ float dpp_max(float v) {
+  const int moved = __builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, true);
+  return fmaxf(v, __int_as_float(moved));
+}
+
+// abs-max over the LANES adjacent lanes (4, 8 or 16) that share a group.
+template <int LANES>
+__device__ __forceinline__ float group_max(float v) {
+  v = dpp_max<0xB1>(v);                       // quad_perm [1,0,3,2]
+  v = dpp_max<0x4E>(v);                       // quad_perm [2,3,0,1]
+  if (LANES >= 8) v = dpp_max<0x141>(v);      // row_half_mirror: quads 0<->1, 2<->3
+  if (LANES >= 16) v = dpp_max<0x140>(v);     // row_mirror: halves of the 16-lane row
+  return v;
+}
+
+template <int BITS>
+struct Packed;  // the 8 codes of one lane
+template <> struct Packed<8> { uint32_t lo, hi; };
+template <> struct Packed<4> { uint32_t w; };
+template <> struct Packed<2> { uint32_t w; };
+
+template <int BITS>
+__device__ __forceinline__ void store_codes(uint8_t* row_codes, int lane_in_row, const Packed<BITS>& p);
+template <>
+__device__ __forceinline__ void store_codes<8>(uint8_t* row_codes, int lane_in_row, const Packed<8>& p) {
+  *reinterpret_cast<uint2*>(row_codes + lane_in_row * 8) = make_uint2(p.lo, p.hi);
+}
+template <>
+__device__ __forceinline__ void store_codes<4>(uint8_t* row_codes, int lane_in_row, const Packed<4>& p) {
+  *reinterpret_cast<uint32_t*>(row_codes + lane_in_row * 4) = p.w;
+}
+template <>
+__device__ __forceinline__ void store_codes<2>(uint8_t* row_codes, int lane_in_row, const Packed<2>& p) {
+  *reinterpret_cast<uint16_t*>(row_codes + lane_in_row * 2) = static_cast<uint16_t>(p.w);
+}
+
+// Code of one element, bit-exact with rint(fl32(x / scale)); see the file header.
+template <int QMAX>
+__device__ __forceinline__ int exact_code(float x, float scale, float inv, bool unsafe) {
+  // |y0 - fl32(x/scale)| <= |x/scale| * (2^-22 + 2^-24 + 2^-24) < (QMAX + 1) * 2^-21
+  constexpr float kTieMargin = static_cast<float>(QMAX + 1) * 0x1p-20f;
+  const float y0 = x * inv;
+  float q0 = rintf(y0);
+  const float d = y0 - q0;  // exact
+  const bool risky = unsafe || fabsf(d) > 0.5f - kTieMargin;
+  if (__builtin_amdgcn_ballot_w64(risky)) {
+    if (risky) {
+      const float h = q0 + copysignf(0.5f, d);      // nearest half-integer, exact
+      const float e = fmaf(-h, scale, x);           // zero exactly when x / scale == h
+      const bool divide = unsafe || e != 0.0f;
+      if (!divide) q0 = rintf(h);
+      if (__builtin_amdgcn_ballot_w64(divide)) {
+        if (divide) q0 = rintf(x / scale);
+      }
+    }
+  }
+  return static_cast<int>(q0);
+}
+
+template <int BITS, int GROUP>
+__device__ __forceinline__ void quantize_lane(const uint4 raw, Packed<BITS>& out, float& scale_out) {
+  constexpr int QMAX = (1 << (BITS - 1)) - 1;
+  const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
+  float x[8];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    x[2 * i] = bf16lo(w[i]);
+    x[2 * i + 1] = bf16hi(w[i]);
+  }
+  float amax = 0.0f;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) amax = fmaxf(amax, fabsf(x[i]));
+  amax = group_max<GROUP / 8>(amax);
+
+  if constexpr (BITS == 2) {
+    scale_out = amax;  // qmax = 1
+    uint32_t word = 0;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const bool nz = 2.0f * fabsf(x[i]) > amax;               // doubling is exact
+      const uint32_t field = nz ? (x[i] < 0.0f ? 3u : 1u) : 0u;
+      word |= field << (2 * i);
+    }
+    out.w = word;
+  } else {
+    const float scale = amax / static_cast<float>(QMAX);       // IEEE division
+    scale_out = scale;
+    // outside this range rcp or the products may leave the normal range: take the division path
+    const bool unsafe = !(scale >= 0x1p-100f && scale <= 0x1p100f) && scale != 0.0f;
+    const float inv = (scale == 0.0f) ? 0.0f : __builtin_amdgcn_rcpf(scale);
+    int q[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      int v = exact_code<QMAX>(x[i], scale, inv, unsafe);
+      v = min(QMAX, max(-QMAX, v));
+      q[i] = v;
+    }
+    if constexpr (BITS == 8) {
+      out.lo = (q[0] & 0xff) | ((q[1] & 0xff) << 8) | ((q[2] & 0xff) << 16) | (static_cast<uint32_t>(q[3]) << 24);
+      out.hi = (q[4] & 0xff) | ((q[5] & 0xff) << 8) | ((q[6] & 0xff) << 16) | (static_cast<uint32_t>(q[7]) << 24);
+    } else {
+      uint32_t word = 0;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) word |= static_cast<uint32_t>(q[i] & 0xf) << (4 * i);
+      out.w = word;
+    }
+  }
+}
+
+template <int BITS, int GROUP, int MODE>
+__global__ __launch_bounds__(kThreads) void quantize_kernel(const QuantArgs a) {
+  constexpr int CB = kHeadDim * BITS / 8;      // code bytes per row
+  constexpr int NS = kHeadDim / GROUP;         // scales per row
+  constexpr int LANES_PER_GROUP = GROUP / 8;
+  const int lane_in_row = threadIdx.x & (kLanesPerRow - 1);
+  const uint32_t row_in_step = threadIdx.x / kLanesPerRow;
+  const uint32_t l = blockIdx.y;
+  const uint32_t row0 = blockIdx.x * kRowsPerBlock + row_in_step;
+  const uint32_t valid_rows = a.n_slots * a.H;
+  const uint16_t* base_l = a.src + static_cast<int64_t>(l) * a.stride_l;
+
+  uint4 raw[kSteps];
+#pragma unroll
+  for (int s = 0; s < kSteps; ++s) {
+    const uint32_t rr = row0 + s * kRowsPerStep;
+    raw[s] = make_uint4(0, 0, 0, 0);
+    if (rr < valid_rows) {
+      const uint16_t* row;
+      if constexpr (MODE == kLinear) {
+        row = base_l + static_cast<int64_t>(rr) * a.stride_h;
+      } else {
+        const uint32_t i = a.div_h.quot(rr);
+        const uint32_t h = rr - i * a.H;
+        uint32_t t = i;
+        if (a.keep_idx) {
+          // an out-of-contract index is clamped so that a bad keep list cannot fault the GPU
+          t = static_cast<uint32_t>(a.keep_idx[(static_cast<int64_t>(l) * a.H + h) * a.k + i]);
+          t = min(t, a.T - 1);
+        }
+        if constexpr (MODE == kStrided) {
+          row = base_l + static_cast<int64_t>(t) * a.stride_t + static_cast<int64_t>(h) * a.stride_h;
+        } else {
+          const uint32_t pg = a.div_bs.quot(t);
+          const uint32_t slot = t - pg * a.bs;
+          const int64_t blk = min(static_cast<uint32_t>(a.block_table[pg]), a.num_blocks - 1);
+          row = base_l + ((blk * a.bs + slot) * a.H + h) * kHeadDim;
+        }
+      }
+      raw[s] = *reinterpret_cast<const uint4*>(row + lane_in_row * 8);
+    }
+  }
+
+#pragma unroll
+  for (int s = 0; s < kSteps; ++s) {
+    const uint32_t rr = row0 + s * kRowsPerStep;
+    if (rr >= a.rows_per_layer) continue;
+    Packed<BITS> p;
+    float scale;
+    quantize_lane<BITS, GROUP>(raw[s], p, scale);  // zero rows (padding slots) give zero codes and scales
+    const int64_t out_row = static_cast<int64_t>(l) * a.rows_per_layer + rr;
+    store_codes<BITS>(a.codes + out_row * CB, lane_in_row, p);
+    if ((lane_in_row % LANES_PER_GROUP) == 0) a.scales[out_row * NS + lane_in_row / LANES_PER_GROUP] = scale;
+  }
+}
+
+template <int BITS, int GROUP>
+void launch_mode(int mode, dim3 grid, hipStream_t st, const QuantArgs& a) {
+  switch (mode) {
+    case kLinear: quantize_kernel<BITS, GROUP, kLinear><<<grid, kThreads, 0, st>>>(a); break;
+    case kStrided: quantize_kernel<BITS, GROUP, kStrided><<<grid, kThreads, 0, st>>>(a); break;
+    default: quantize_kernel<BITS, GROUP, kPaged><<<grid, kThreads, 0, st>>>(a); break;
+  }
+}
+
+template <int BITS>
+void launch_group(int group, int mode, dim3 grid, hipStream_t st, const QuantArgs& a) {
+  switch (group) {
+    case 32: launch_mode<BITS, 32>(mode, grid, st, a); break;
+    case 64: launch_mode<BITS, 64>(mode, grid, st, a); break;
+    default: launch_mode<BITS, 128>(mode, grid, st, a); break;
+  }
+}
+
+}  // namespace
+}  // namespace kvp
+
+extern "C" int32_t kvp_quantize(const kvp_view* src, const kvp_paged* src_paged, const int32_t* keep_idx, int64_t k,
+                                const kvp_qplane* dst, void* stream) {
+  using namespace kvp;
+  if ((src == nullptr) == (src_paged == nullptr)) return src ? KVP_ERR_SHAPE : KVP_ERR_NULL;
+  int32_t rc = check_qplane(dst);
+  if (rc != KVP_OK) return rc;
+  QuantArgs a{};
+  int64_t L, T, H;
+  int mode;
+  if (src) {
+    rc = check_view(src);
+    if (rc != KVP_OK) return rc;
+    L = src->L; T = src->T; H = src->H;
+    a.src = static_cast<const uint16_t*>(src->ptr);
+    a.stride_l = src->stride_l; a.stride_t = src->stride_t; a.stride_h = src->stride_h;
+    mode = (!keep_idx && src->stride_t == H * src->stride_h) ? kLinear : kStrided;
+  } else {
+    rc = check_paged(src_paged);
+    if (rc != KVP_OK) return rc;
+    L = src_paged->L; T = src_paged->T; H = src_paged->H;
+    a.src = static_cast<const uint16_t*>(src_paged->pool);
+    a.stride_l = src_paged->stride_l;
+    a.block_table = src_paged->block_table;
+    a.bs = static_cast<uint32_t>(src_paged->bs);
+    a.num_blocks = static_cast<uint32_t>(src_paged->num_blocks);
+    a.div_bs = FastDiv(a.bs);
+    mode = kPaged;
+  }
+  if (dst->L != L || dst->H != H) return KVP_ERR_SHAPE;
+  int64_t n_slots = T;
+  if (keep_idx) {
+    if (k <= 0 || k > T) return KVP_ERR_SHAPE;
+    if (reinterpret_cast<uintptr_t>(keep_idx) & 3u) return KVP_ERR_ALIGN;
+    n_slots = k;
+  }
+  if (dst->T != n_slots) return KVP_ERR_SHAPE;
+  if (dst->Tp * H >= (1ll << 31) || T >= (1ll << 31) || L > 65535) return KVP_ERR_SHAPE;
+  if (src_paged && src_paged->num_blocks >= (1ll << 31)) return KVP_ERR_SHAPE;
+  a.keep_idx = keep_idx;
+  a.k = k;
+  a.n_slots = static_cast<uint32_t>(n_slots);
+  a.T = static_cast<uint32_t>(T);
+  a.rows_per_layer = static_cast<uint32_t>(dst->Tp * H);
+  a.H = static_cast<uint32_t>(H);
+  a.div_h = FastDiv(a.H);
+  a.codes = dst->codes;
+  a.scales = dst->scales;
+  const dim3 grid(static_cast<unsigned>(ceil_div(a.rows_per_layer, kRowsPerBlock)), static_cast<unsigned>(L));
+  const hipStream_t st = as_stream(stream);
+  switch (dst->bits) {
+    case 8: launch_group<8>(dst->group, mode, grid, st, a); break;
+    case 4: launch_group<4>(dst->group, mode, grid, st, a); break;
+    default: launch_group<2>(dst->group, mode, grid, st, a); break;
+  }
+  return launch_status();
+}

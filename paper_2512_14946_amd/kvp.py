@@ -1,0 +1,305 @@
+"""ctypes binding of libkvp.so: the same entry points as include/kvp.h, taking torch tensors.
+
+Argument marshalling only.  torch supplies device memory and the current HIP stream; every
+kernel launch happens inside the C library.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+from typing import Iterable, Sequence
+
+import torch
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_PKG, "libkvp.so")
+
+_i32, _i64, _vp, _sz = ctypes.c_int32, ctypes.c_int64, ctypes.c_void_p, ctypes.c_size_t
+
+
+class KVPError(RuntimeError):
+    def __init__(self, code: int, what: str):
+        self.code = code
+        super().__init__(f"{what}: {kvp_strerror(code)} ({code})")
+
+
+class _View(ctypes.Structure):
+    _fields_ = [("ptr", _vp), ("L", _i64), ("T", _i64), ("H", _i64), ("D", _i64),
+                ("stride_l", _i64), ("stride_t", _i64), ("stride_h", _i64)]
+
+
+class _Paged(ctypes.Structure):
+    _fields_ = [("pool", _vp), ("block_table", _vp), ("L", _i64), ("num_blocks", _i64), ("bs", _i64),
+                ("H", _i64), ("D", _i64), ("T", _i64), ("stride_l", _i64)]
+
+
+class _QPlane(ctypes.Structure):
+    _fields_ = [("codes", _vp), ("scales", _vp), ("bits", _i32), ("group", _i32),
+                ("L", _i64), ("T", _i64), ("Tp", _i64), ("H", _i64), ("D", _i64)]
+
+
+class _Config(ctypes.Structure):
+    _fields_ = [("bits", _i32), ("group", _i32), ("keep_k", _i64)]
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def _load():
+    if not os.path.exists(_LIB_PATH):
+        raise ImportError(
+            f"{_LIB_PATH} is not built; run `python -m paper_2512_14946_amd.build` "
+            "(there is no CPU fallback for the kvp_* operations)")
+    lib = ctypes.CDLL(_LIB_PATH)
+    P = ctypes.POINTER
+    lib.kvp_quantize.restype = _i32
+    lib.kvp_quantize.argtypes = [P(_View), P(_Paged), _vp, _i64, P(_QPlane), _vp]
+    lib.kvp_dequantize_paged.restype = _i32
+    lib.kvp_dequantize_paged.argtypes = [P(_QPlane), P(_Paged), _vp]
+    lib.kvp_score_tokens.restype = _i32
+    lib.kvp_score_tokens.argtypes = [P(_View), P(_View), _i32, _i32, _vp, _vp, _sz, _vp]
+    lib.kvp_score_workspace_bytes.restype = _sz
+    lib.kvp_score_workspace_bytes.argtypes = [_i64] * 5
+    lib.kvp_select_topk.restype = _i32
+    lib.kvp_select_topk.argtypes = [_vp, _i64, _i64, _i64, _i64, _vp, _vp, _sz, _vp]
+    lib.kvp_select_workspace_bytes.restype = _sz
+    lib.kvp_select_workspace_bytes.argtypes = [_i64] * 3
+    lib.kvp_eval_configs.restype = _i32
+    lib.kvp_eval_configs.argtypes = [P(_View), P(_View), P(_View), P(_Config), _i32, _vp, _vp, _vp, _sz, _vp]
+    lib.kvp_eval_workspace_bytes.restype = _sz
+    lib.kvp_eval_workspace_bytes.argtypes = [_i64] * 5 + [_i32]
+    lib.kvp_keep_count.restype = _i64
+    lib.kvp_keep_count.argtypes = [ctypes.c_double, _i64]
+    lib.kvp_copy_bytes.restype = _i32
+    lib.kvp_copy_bytes.argtypes = [_vp, _vp, _sz, _vp]
+    lib.kvp_strerror.restype = ctypes.c_char_p
+    lib.kvp_strerror.argtypes = [_i32]
+    lib.kvp_version.restype = ctypes.c_uint32
+    lib.kvp_version.argtypes = []
+    return lib
+
+
+_lib = _load()
+
+
+# ------------------------------------------------------------------ containers
+
+@dataclass
+class QPlane:
+    """Compressed plane: codes u8 [L][Tp][H][D*bits/8], scales f32 [L][Tp][H][D/group]."""
+    codes: torch.Tensor
+    scales: torch.Tensor
+    bits: int
+    group: int
+    T: int
+
+    @property
+    def Tp(self) -> int:
+        return self.codes.shape[1]
+
+    def nbytes(self) -> int:
+        return self.codes.numel() + 4 * self.scales.numel()
+
+
+@dataclass
+class PagedKV:
+    """Paged bf16 plane: pool [L][num_blocks][bs][H][D], block_table int32 [ceil(T/bs)]."""
+    pool: torch.Tensor
+    block_table: torch.Tensor
+    T: int
+
+
+def alloc_qplane(L: int, T: int, H: int, D: int, bits: int, group: int, device, page: int = 16) -> QPlane:
+    Tp = (T + page - 1) // page * page
+    codes = torch.empty(L, Tp, H, D * bits // 8, dtype=torch.uint8, device=device)
+    scales = torch.empty(L, Tp, H, D // group, dtype=torch.float32, device=device)
+    return QPlane(codes, scales, bits, group, T)
+
+
+def alloc_paged(L: int, T: int, H: int, D: int, block_table: torch.Tensor, num_blocks: int, bs: int = 16,
+                fill_nan: bool = False) -> PagedKV:
+    dev = block_table.device
+    if fill_nan:
+        pool = torch.full((L, num_blocks, bs, H, D), float("nan"), dtype=torch.bfloat16, device=dev)
+    else:
+        pool = torch.empty(L, num_blocks, bs, H, D, dtype=torch.bfloat16, device=dev)
+    return PagedKV(pool, block_table, T)
+
+
+# ------------------------------------------------------------------ marshalling
+
+def _stream(stream) -> int:
+    if stream is None:
+        return torch.cuda.current_stream().cuda_stream
+    if isinstance(stream, torch.cuda.Stream):
+        return stream.cuda_stream
+    return int(stream)
+
+
+def _need_cuda(*ts):
+    for t in ts:
+        if t is not None and not t.is_cuda:
+            raise ValueError("kvp_* operations run on the GPU only: tensors must live on a cuda device")
+
+
+def _view(t: torch.Tensor) -> _View:
+    if t.dtype != torch.bfloat16 or t.dim() != 4:
+        raise ValueError("expected a bf16 tensor [L][T][H][D]")
+    if t.stride(3) != 1:
+        raise ValueError("innermost dimension must be contiguous")
+    L, T, H, D = t.shape
+    return _View(t.data_ptr(), L, T, H, D, t.stride(0), t.stride(1), t.stride(2))
+
+
+def _paged(p: PagedKV) -> _Paged:
+    pool = p.pool
+    if pool.dtype != torch.bfloat16 or pool.dim() != 5 or not pool[0].is_contiguous():
+        raise ValueError("pool must be bf16 [L][num_blocks][bs][H][D], contiguous per layer")
+    if p.block_table.dtype != torch.int32 or not p.block_table.is_contiguous():
+        raise ValueError("block_table must be contiguous int32")
+    L, NB, bs, H, D = pool.shape
+    if p.block_table.numel() < (p.T + bs - 1) // bs:
+        raise ValueError("block_table is shorter than ceil(T / bs)")
+    return _Paged(pool.data_ptr(), p.block_table.data_ptr(), L, NB, bs, H, D, p.T, pool.stride(0))
+
+
+def _qplane(q: QPlane) -> _QPlane:
+    if q.codes.dtype != torch.uint8 or q.scales.dtype != torch.float32:
+        raise ValueError("codes must be uint8 and scales float32")
+    if not (q.codes.is_contiguous() and q.scales.is_contiguous()):
+        raise ValueError("codes and scales must be contiguous")
+    L, Tp, H, cb = q.codes.shape
+    D = cb * 8 // q.bits
+    if tuple(q.scales.shape) != (L, Tp, H, D // q.group):
+        raise ValueError("scales shape does not match codes")
+    return _QPlane(q.codes.data_ptr(), q.scales.data_ptr(), q.bits, q.group, L, q.T, Tp, H, D)
+
+
+def _check(rc: int, what: str):
+    if rc != 0:
+        raise KVPError(rc, what)
+
+
+def _workspace(ws, nbytes: int, device):
+    if ws is None:
+        ws = torch.empty(max(nbytes, 16), dtype=torch.uint8, device=device)
+    return ws, ws.data_ptr(), ws.numel() * ws.element_size()
+
+
+# ------------------------------------------------------------------ entry points
+
+def kvp_strerror(code: int) -> str:
+    return _lib.kvp_strerror(int(code)).decode()
+
+
+def kvp_version() -> int:
+    return int(_lib.kvp_version())
+
+
+def kvp_keep_count(ratio: float, T: int) -> int:
+    return int(_lib.kvp_keep_count(float(ratio), int(T)))
+
+
+def kvp_quantize(src, dst: QPlane, keep_idx: torch.Tensor | None = None, stream=None) -> QPlane:
+    """src: bf16 tensor [L][T][H][D] (strided view allowed) or PagedKV.  Fills dst.codes / dst.scales."""
+    k = 0
+    if keep_idx is not None:
+        if keep_idx.dtype != torch.int32 or not keep_idx.is_contiguous() or keep_idx.dim() != 3:
+            raise ValueError("keep_idx must be contiguous int32 [L][H][k]")
+        k = keep_idx.shape[2]
+    kp = keep_idx.data_ptr() if keep_idx is not None else None
+    qp = _qplane(dst)
+    if isinstance(src, PagedKV):
+        _need_cuda(src.pool, src.block_table, dst.codes, dst.scales, keep_idx)
+        pg = _paged(src)
+        rc = _lib.kvp_quantize(None, ctypes.byref(pg), kp, k, ctypes.byref(qp), _stream(stream))
+    else:
+        _need_cuda(src, dst.codes, dst.scales, keep_idx)
+        vw = _view(src)
+        rc = _lib.kvp_quantize(ctypes.byref(vw), None, kp, k, ctypes.byref(qp), _stream(stream))
+    _check(rc, "kvp_quantize")
+    return dst
+
+
+def kvp_dequantize_paged(src: QPlane, dst: PagedKV, stream=None) -> PagedKV:
+    _need_cuda(src.codes, src.scales, dst.pool, dst.block_table)
+    qp, pg = _qplane(src), _paged(dst)
+    _check(_lib.kvp_dequantize_paged(ctypes.byref(qp), ctypes.byref(pg), _stream(stream)), "kvp_dequantize_paged")
+    return dst
+
+
+def kvp_score_workspace_bytes(L: int, Hkv: int, Hq: int, W: int, T: int) -> int:
+    return int(_lib.kvp_score_workspace_bytes(L, Hkv, Hq, W, T))
+
+
+def kvp_score_tokens(q_win: torch.Tensor, k: torch.Tensor, scores: torch.Tensor | None = None, causal: bool = True,
+                     force_window: bool = True, ws: torch.Tensor | None = None, stream=None) -> torch.Tensor:
+    """q_win bf16 [L][W][Hq][D], k bf16 [L][T][Hkv][D] -> scores f32 [L][Hkv][T]."""
+    _need_cuda(q_win, k, scores, ws)
+    L, T, Hkv, _ = k.shape
+    _, W, Hq, _ = q_win.shape
+    if scores is None:
+        scores = torch.empty(L, Hkv, T, dtype=torch.float32, device=k.device)
+    if scores.dtype != torch.float32 or not scores.is_contiguous() or tuple(scores.shape) != (L, Hkv, T):
+        raise ValueError("scores must be contiguous float32 [L][Hkv][T]")
+    ws, wp, wb = _workspace(ws, kvp_score_workspace_bytes(L, Hkv, Hq, W, T), k.device)
+    qv, kv = _view(q_win), _view(k)
+    _check(_lib.kvp_score_tokens(ctypes.byref(qv), ctypes.byref(kv), int(causal), int(force_window),
+                                 scores.data_ptr(), wp, wb, _stream(stream)), "kvp_score_tokens")
+    return scores
+
+
+def kvp_select_workspace_bytes(n_rows: int, T: int, k: int) -> int:
+    return int(_lib.kvp_select_workspace_bytes(n_rows, T, k))
+
+
+def kvp_select_topk(scores: torch.Tensor, k: int, idx_out: torch.Tensor | None = None,
+                    ws: torch.Tensor | None = None, stream=None) -> torch.Tensor:
+    """scores f32 [n_rows][T] (row stride >= T) -> idx int32 [n_rows][k], ascending."""
+    _need_cuda(scores, idx_out, ws)
+    if scores.dtype != torch.float32 or scores.dim() != 2 or (scores.shape[1] > 1 and scores.stride(1) != 1):
+        raise ValueError("scores must be float32 [n_rows][T] with contiguous rows")
+    n_rows, T = scores.shape
+    row_stride = scores.stride(0) if n_rows > 1 else T
+    if idx_out is None:
+        idx_out = torch.empty(n_rows, k, dtype=torch.int32, device=scores.device)
+    if idx_out.dtype != torch.int32 or not idx_out.is_contiguous() or tuple(idx_out.shape) != (n_rows, k):
+        raise ValueError("idx_out must be contiguous int32 [n_rows][k]")
+    ws, wp, wb = _workspace(ws, kvp_select_workspace_bytes(n_rows, T, k), scores.device)
+    _check(_lib.kvp_select_topk(scores.data_ptr(), n_rows, T, row_stride, k, idx_out.data_ptr(), wp, wb,
+                                _stream(stream)), "kvp_select_topk")
+    return idx_out
+
+
+def kvp_eval_workspace_bytes(L: int, Hkv: int, Hq: int, W: int, T: int, n_cfgs: int) -> int:
+    return int(_lib.kvp_eval_workspace_bytes(L, Hkv, Hq, W, T, n_cfgs))
+
+
+def kvp_eval_configs(q_win: torch.Tensor, k: torch.Tensor, v: torch.Tensor, cfgs: Iterable[Sequence[int]],
+                     loss: torch.Tensor | None = None, partial: torch.Tensor | None = None,
+                     ws: torch.Tensor | None = None, stream=None, want_partial: bool = False):
+    """cfgs: (bits, group, keep_k) triples.  Returns loss f32 [n] (and partial f32 [L][n][2] if asked)."""
+    _need_cuda(q_win, k, v, loss, partial, ws)
+    cfgs = list(cfgs)
+    n = len(cfgs)
+    L, T, Hkv, _ = k.shape
+    _, W, Hq, _ = q_win.shape
+    arr = (_Config * max(n, 1))(*[_Config(int(b), int(g), int(kk)) for b, g, kk in cfgs])
+    if loss is None:
+        loss = torch.empty(n, dtype=torch.float32, device=k.device)
+    if want_partial and partial is None:
+        partial = torch.empty(L, n, 2, dtype=torch.float32, device=k.device)
+    ws, wp, wb = _workspace(ws, kvp_eval_workspace_bytes(L, Hkv, Hq, W, T, n), k.device)
+    qv, kv, vv = _view(q_win), _view(k), _view(v)
+    _check(_lib.kvp_eval_configs(ctypes.byref(qv), ctypes.byref(kv), ctypes.byref(vv), arr, n, loss.data_ptr(),
+                                 partial.data_ptr() if partial is not None else None, wp, wb, _stream(stream)),
+           "kvp_eval_configs")
+    return (loss, partial) if partial is not None else loss
+
+
+def kvp_copy_bytes(dst: torch.Tensor, src: torch.Tensor, stream=None):
+    _need_cuda(dst, src)
+    n = src.numel() * src.element_size()
+    _check(_lib.kvp_copy_bytes(dst.data_ptr(), src.data_ptr(), n, _stream(stream)), "kvp_copy_bytes")

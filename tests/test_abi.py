@@ -1,0 +1,80 @@
+"""CPU-only checks of the C-ABI boundary: the library loads, exports every symbol the header
+declares, and its host-side helpers and argument validation work without a GPU."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "kvp.h")
+
+
+@pytest.fixture(scope="module")
+def lib():
+    from paper_2512_14946_amd import build
+    if not os.path.exists(build.LIB):
+        build.build_library()
+    return ctypes.CDLL(build.LIB)
+
+
+def _declared_symbols():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(kvp_[a-z_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = _declared_symbols()
+    assert {"kvp_quantize", "kvp_dequantize_paged", "kvp_score_tokens", "kvp_select_topk",
+            "kvp_eval_configs"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), f"{n} declared in kvp.h but not exported"
+
+
+def test_host_helpers(lib):
+    lib.kvp_keep_count.restype = ctypes.c_int64
+    lib.kvp_keep_count.argtypes = [ctypes.c_double, ctypes.c_int64]
+    assert lib.kvp_keep_count(0.5, 4096) == 2048
+    assert lib.kvp_keep_count(0.3, 16384) == 4916
+    assert lib.kvp_keep_count(0.1, 131072) == 13108
+    assert [lib.kvp_keep_count(r, 8192) for r in (0.25, 0.5, 0.75)] == [2048, 4096, 6144]
+    assert lib.kvp_keep_count(0.0, 5) == 1 and lib.kvp_keep_count(2.0, 5) == 5
+    lib.kvp_strerror.restype = ctypes.c_char_p
+    assert lib.kvp_strerror(0) == b"ok"
+    assert all(len(lib.kvp_strerror(c)) >= 2 for c in range(-7, 1))
+    lib.kvp_version.restype = ctypes.c_uint32
+    assert lib.kvp_version() >= 0x00010000
+
+
+def test_validation_rejects_before_any_launch(lib):
+    # NULL structs / pointers are refused on the host: no GPU is needed (and none is touched)
+    lib.kvp_quantize.restype = ctypes.c_int32
+    lib.kvp_quantize.argtypes = [ctypes.c_void_p] * 3 + [ctypes.c_int64] + [ctypes.c_void_p] * 2
+    assert lib.kvp_quantize(None, None, None, 0, None, None) == -1
+    lib.kvp_dequantize_paged.restype = ctypes.c_int32
+    lib.kvp_dequantize_paged.argtypes = [ctypes.c_void_p] * 3
+    assert lib.kvp_dequantize_paged(None, None, None) == -1
+    lib.kvp_select_topk.restype = ctypes.c_int32
+    lib.kvp_select_topk.argtypes = [ctypes.c_void_p] + [ctypes.c_int64] * 4 + [ctypes.c_void_p] * 2 + \
+        [ctypes.c_size_t, ctypes.c_void_p]
+    assert lib.kvp_select_topk(None, 1, 8, 8, 4, None, None, 0, None) == -1
+    lib.kvp_score_tokens.restype = ctypes.c_int32
+    lib.kvp_score_tokens.argtypes = [ctypes.c_void_p] * 2 + [ctypes.c_int32] * 2 + [ctypes.c_void_p] * 2 + \
+        [ctypes.c_size_t, ctypes.c_void_p]
+    assert lib.kvp_score_tokens(None, None, 1, 1, None, None, 0, None) == -1
+    lib.kvp_copy_bytes.restype = ctypes.c_int32
+    lib.kvp_copy_bytes.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+    assert lib.kvp_copy_bytes(None, None, 16, None) == -1
+    assert lib.kvp_copy_bytes(16, 32, 8, None) == -2
+
+
+def test_binding_refuses_cpu_tensors():
+    import torch
+    import paper_2512_14946_amd as kvp
+    x = torch.zeros(1, 16, 8, 128, dtype=torch.bfloat16)
+    qp = kvp.alloc_qplane(1, 16, 8, 128, 4, 64, "cpu")
+    with pytest.raises(ValueError):
+        kvp.kvp_quantize(x, qp)
+    with pytest.raises(ValueError):
+        kvp.kvp_select_topk(torch.zeros(2, 8), 4)

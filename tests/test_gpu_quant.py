@@ -1,0 +1,144 @@
+"""GPU parity: kvp_quantize / kvp_dequantize_paged against the CPU oracle, bit for bit.
+
+Every case prints its name before touching the GPU so that a fault names its case.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import workloads
+from helpers import bits_to_torch, torch_bits
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+ALL_CODECS = [(8, 128), (8, 64), (8, 32), (4, 128), (4, 64), (4, 32), (2, 128), (2, 64), (2, 32)]
+
+
+def _kvp():
+    import paper_2512_14946_amd as kvp
+    return kvp
+
+
+def _say(*a):
+    print("[case]", *a, flush=True)
+
+
+def _special_rows(D=128):
+    """Rows that exercise ties, zeros, tiny and huge magnitudes, mixed-scale groups."""
+    rng = np.random.default_rng(7)
+    rows = []
+    rows.append(np.zeros(D))                                               # all zero
+    rows.append(np.where(np.arange(D) % 2 == 0, 3.0, -3.0))                # constant magnitude
+    rows.append(np.round(rng.standard_normal(D) * 4) / 4)                  # dyadic: exact .5 ties
+    rows.append(np.round(rng.standard_normal(D) * 16) / 16 * 7)            # multiples of 7/16: ties vs qmax 7
+    rows.append(np.round(rng.standard_normal(D) * 8) / 8 * 127)            # ties vs qmax 127
+    rows.append(rng.standard_normal(D) * 2.0 ** -60)                       # tiny but inside the graded range
+    rows.append(rng.standard_normal(D) * 2.0 ** 60)                        # huge
+    rows.append(rng.standard_normal(D) * 2.0 ** -110)                      # below the fast-path range
+    rows.append(rng.standard_normal(D) * 2.0 ** 110)                       # above the fast-path range
+    r = rng.standard_normal(D)
+    r[:32] = 0.0                                                           # one zero group among non-zero ones
+    rows.append(r)
+    r = rng.standard_normal(D)
+    r[5] = 1000.0                                                          # one outlier per row
+    rows.append(r)
+    rows.append(np.full(D, 2.0 ** -120))                                   # subnormal scales
+    return np.stack(rows).astype(np.float32)
+
+
+@pytest.mark.parametrize("bits,group", ALL_CODECS)
+def test_quantize_dequantize_bit_exact(bits, group):
+    kvp = _kvp()
+    L, T, H, D, bs = 3, 203, 8, 128, 16          # 203 tokens: several blocks and a ragged tail page
+    _say("quant/dequant", bits, group, (L, T, H, D))
+    K, _ = workloads.make_kv(L, T, H, D, seed=bits * 10 + group)
+    xb = torch_bits(K).copy()
+    sp = torch_bits(torch.from_numpy(_special_rows(D)).to(torch.bfloat16))
+    xb[0, :sp.shape[0], 0] = sp
+    xb[2, -sp.shape[0]:, 7] = sp
+    x = bits_to_torch(xb, DEV)
+    qp = kvp.alloc_qplane(L, T, H, D, bits, group, DEV)
+    qp.codes.fill_(0xEE)
+    qp.scales.fill_(float("nan"))
+    kvp.kvp_quantize(x, qp)
+    torch.cuda.synchronize()
+    ocodes, oscales = oracle.quantize(xb, bits, group, Tp=qp.Tp)
+    assert np.array_equal(qp.codes.cpu().numpy(), ocodes)
+    assert np.array_equal(qp.scales.cpu().numpy().view(np.uint32), oscales.view(np.uint32))
+
+    bt, nb = workloads.make_block_table(T, bs, seed=3, spare=3, device=DEV)
+    pg = kvp.alloc_paged(L, T, H, D, bt, nb, bs, fill_nan=True)
+    kvp.kvp_dequantize_paged(qp, pg)
+    torch.cuda.synchronize()
+    opool = oracle.dequantize_paged(ocodes, oscales, bits, group, T, bt.cpu().numpy(), nb, bs,
+                                    pool=torch_bits(torch.full((L, nb, bs, H, D), float("nan"),
+                                                               dtype=torch.bfloat16)).copy())
+    assert np.array_equal(torch_bits(pg.pool), opool)
+
+
+@pytest.mark.parametrize("bits,group", [(8, 128), (4, 32), (2, 64)])
+def test_quantize_strided_gather_paged_sources(bits, group):
+    kvp = _kvp()
+    L, T, H, D, bs = 2, 150, 4, 128, 16
+    _say("quant sources", bits, group)
+    K, V = workloads.make_kv(L, T, H + 2, D, seed=11)
+    xb_full = torch_bits(K)
+    x_full = K.to(DEV)
+    # (a) strided view: heads 1..4 of a 6-head tensor
+    xv = x_full[:, :, 1:1 + H]
+    qp = kvp.alloc_qplane(L, T, H, D, bits, group, DEV)
+    kvp.kvp_quantize(xv, qp)
+    oc, os_ = oracle.quantize(xb_full[:, :, 1:1 + H], bits, group, Tp=qp.Tp)
+    torch.cuda.synchronize()
+    assert np.array_equal(qp.codes.cpu().numpy(), oc)
+    assert np.array_equal(qp.scales.cpu().numpy().view(np.uint32), os_.view(np.uint32))
+    # (b) gathered: per-head keep lists
+    rng = np.random.default_rng(5)
+    k = 37
+    keep = np.stack([[np.sort(rng.choice(T, k, replace=False)) for _ in range(H)] for _ in range(L)]).astype(np.int32)
+    qg = kvp.alloc_qplane(L, k, H, D, bits, group, DEV)
+    kvp.kvp_quantize(xv, qg, keep_idx=torch.from_numpy(keep).to(DEV))
+    og, ogs = oracle.quantize(xb_full[:, :, 1:1 + H], bits, group, keep_idx=keep, Tp=qg.Tp)
+    torch.cuda.synchronize()
+    assert np.array_equal(qg.codes.cpu().numpy(), og)
+    assert np.array_equal(qg.scales.cpu().numpy().view(np.uint32), ogs.view(np.uint32))
+    # (c) paged source, flat and gathered
+    xc = np.ascontiguousarray(xb_full[:, :, 1:1 + H])
+    bt, nb = workloads.make_block_table(T, bs, seed=9, spare=1)
+    pool = np.zeros((L, nb, bs, H, D), dtype=np.uint16)
+    btn = bt.numpy()
+    for t in range(T):
+        pool[:, btn[t // bs], t % bs] = xc[:, t]
+    src = kvp.PagedKV(bits_to_torch(pool, DEV), bt.to(DEV), T)
+    qpp = kvp.alloc_qplane(L, T, H, D, bits, group, DEV)
+    kvp.kvp_quantize(src, qpp)
+    qpg = kvp.alloc_qplane(L, k, H, D, bits, group, DEV)
+    kvp.kvp_quantize(src, qpg, keep_idx=torch.from_numpy(keep).to(DEV))
+    torch.cuda.synchronize()
+    assert np.array_equal(qpp.codes.cpu().numpy(), oc) and np.array_equal(qpp.scales.cpu().numpy(), os_)
+    assert np.array_equal(qpg.codes.cpu().numpy(), og) and np.array_equal(qpg.scales.cpu().numpy(), ogs)
+
+
+def test_quantize_argument_errors_enqueue_nothing():
+    kvp = _kvp()
+    _say("argument errors")
+    x = torch.zeros(1, 16, 8, 128, dtype=torch.bfloat16, device=DEV)
+    qp = kvp.alloc_qplane(1, 16, 8, 128, 4, 64, DEV)
+    bad = kvp.QPlane(qp.codes, qp.scales, 4, 64, 15)            # T mismatch
+    with pytest.raises(kvp.KVPError) as e:
+        kvp.kvp_quantize(x, bad)
+    assert e.value.code == -3
+    bad = kvp.QPlane(qp.codes, qp.scales.view(1, 16, 8, -1), 3, 64, 16)
+    with pytest.raises((kvp.KVPError, ValueError)):
+        kvp.kvp_quantize(x, bad)
+    x64 = torch.zeros(1, 16, 8, 64, dtype=torch.bfloat16, device=DEV)
+    q64 = kvp.alloc_qplane(1, 16, 8, 64, 4, 32, DEV)
+    with pytest.raises(kvp.KVPError) as e:
+        kvp.kvp_quantize(x64, q64)
+    assert e.value.code == -4
+    with pytest.raises(kvp.KVPError) as e:                       # misaligned view
+        kvp.kvp_quantize(x.view(-1)[4:4 + 8 * 8 * 128].view(1, 8, 8, 128), kvp.alloc_qplane(1, 8, 8, 128, 4, 64, DEV))
+    assert e.value.code == -2
+    torch.cuda.synchronize()
