@@ -1,7 +1,441 @@
-// placeholder until the configuration-evaluation kernels land
-#include "kvp_common.h"
-extern "C" size_t kvp_eval_workspace_bytes(int64_t, int64_t, int64_t, int64_t, int64_t, int32_t) { return 0; }
-extern "C" int32_t kvp_eval_configs(const kvp_view*, const kvp_view*, const kvp_view*, const kvp_config*, int32_t,
-                                    float*, float*, void*, size_t, void*) {
-  return KVP_ERR_UNSUPPORTED;
+// kvp_eval_configs: quality-loss proxy of every candidate (bits, group, keep_k) configuration of one
+// context (the paper's profiler compresses a KV cache "with different methods and ratios" and
+// scores every version; this is the quality term of its utility function with the attention-output
+// error standing in for the answer-similarity metric that needs model weights).
+//
+//   loss[c] = sqrt( sum (O_c - O_full)^2 / sum O_full^2 ),  O = softmax(Q K^T / sqrt(D)) V
+//
+// Pipeline (all on the caller's stream, scratch in the caller's workspace):
+//   1. token scores of the unquantized K (kvp_score_tokens, causal, window forced);
+//   2. one top-k keep list per distinct keep_k < T (kvp_select_topk's kernel);
+//   3. reference pass: O_full and sum O_full^2 per (layer, kv head, 128-row block);
+//   4. one "stream" per distinct (bits, group, keep_k): attention of the window rows over the kept
+//      tokens with K and V quantized and dequantized on the fly, compared with O_full;
+//   5. a single-block reduction in a fixed order (deterministic) to loss[] and partial[].
+//
+// The attention kernel (steps 3 and 4) walks the kept tokens in tiles of 32.  Per tile: 256 threads
+// load 32 K rows and 32 V rows (16 lanes per row, 8 channels per lane), run the bit-exact group
+// quantizer and dequantizer of quant_device.h on them, and stage K-hat as bf16 and V-hat as fp32
+// in LDS.  Each of the 4 waves owns 32 of the block's 128 query rows (stationary MFMA operand in
+// registers) and computes S^T = K-hat Q^T with 8 v_mfma_f32_32x32x16_bf16, so a lane holds one
+// query and 16 keys and the online-softmax statistics stay lane-private.  The probabilities go to
+// LDS in fp32 and the P.V product runs on the vector ALU in fp32 with an 8x8 register tile per
+// thread (the loss is a difference of two nearly equal outputs: rounding P to bf16 for a matrix
+// instruction would swamp the int8 configurations).
+
+#include "kvp_internal.h"
+#include "quant_device.h"
+
+namespace kvp {
+namespace {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(16))) float floatx16;
+
+constexpr int kThreads = 256;
+constexpr int kTile = 32;                  // tokens per tile
+constexpr int kRowsPerBlock = 128;         // query rows per block
+constexpr int kPitch = 136;                // bf16 elements per staged K row (272 B)
+constexpr int kMaxCfgs = 64;
+constexpr int kMaxLevels = 8;
+constexpr float kLog2e = 1.4426950408889634f;
+
+struct StreamDesc {
+  int32_t bits, group;   // bits == 16: no quantization
+  int32_t level;         // index into EvalArgs::level_k / level_idx
+};
+
+struct EvalArgs {
+  const uint16_t* q;
+  int64_t q_sl, q_st, q_sh;
+  const uint16_t* k;
+  int64_t k_sl, k_st, k_sh;
+  const uint16_t* v;
+  int64_t v_sl, v_st, v_sh;
+  int32_t T, W, G, Hkv, M, RB, L;
+  float scale2;
+  int32_t n_streams, n_cfgs, n_levels;
+  int32_t level_k[kMaxLevels];
+  const int32_t* level_idx[kMaxLevels];  // [L*Hkv][k] ascending keep list, or null = all tokens in order
+  StreamDesc streams[kMaxCfgs];
+  uint8_t cfg_stream[kMaxCfgs];
+  float* o_full;    // [L*Hkv][RB][128][128]
+  float* den_part;  // [L*Hkv][RB]
+  float* num_part;  // [L*Hkv][RB][n_streams]
+  float* loss;      // [n_cfgs]
+  float* partial;   // [L][n_cfgs][2] or null
+};
+
+__device__ __forceinline__ bf16x8 as_bf16x8(uint4 v) {
+  union { uint4 u; bf16x8 b; } c;
+  c.u = v;
+  return c.b;
+}
+
+__device__ __forceinline__ int acc_row(int lane, int v) { return (lane >> 5) * 4 + (v >> 2) * 8 + (v & 3); }
+
+// One lane's 8 channels of a row through quantize -> dequantize at (bits, group): y holds the
+// values decoding would read back (exactly representable in bf16).  bits and group are uniform
+// across the block.
+__device__ __forceinline__ void fake_quant8(const uint4 raw, int bits, int group, float y[8]) {
+  float x[8];
+  unpack_bf16x8(raw, x);
+  if (bits == 16) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) y[i] = x[i];
+    return;
+  }
+  const float amax = group_max(abs_max8(x), group / 8);
+  if (bits == 2) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) y[i] = static_cast<float>(ternary_code(x[i], amax)) * amax;
+  } else if (bits == 4) {
+    const GroupScale<7> gs(amax);
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+      y[i] = __uint_as_float(f32_to_bf16_bits(static_cast<float>(gs.code(x[i])) * gs.scale) << 16);
+  } else {
+    const GroupScale<127> gs(amax);
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+      y[i] = __uint_as_float(f32_to_bf16_bits(static_cast<float>(gs.code(x[i])) * gs.scale) << 16);
+  }
+}
+
+__device__ __forceinline__ float block_sum(float v, float* red) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+  __syncthreads();
+  return red[0] + red[1] + red[2] + red[3];
+}
+
+// REFERENCE: stream = (16 bits, all tokens); writes O_full and the denominator.
+template <bool REFERENCE>
+__global__ __launch_bounds__(kThreads) void attention_kernel(const EvalArgs a) {
+  __shared__ __attribute__((aligned(16))) uint16_t k_s[kTile * kPitch];
+  __shared__ __attribute__((aligned(16))) float v_s[kTile * kHeadDim];
+  __shared__ __attribute__((aligned(16))) float p_s[kTile * kRowsPerBlock];
+  __shared__ __attribute__((aligned(16))) float alpha_s[kRowsPerBlock];
+  __shared__ __attribute__((aligned(16))) float z_s[kRowsPerBlock];
+  __shared__ int tok_s[kTile];
+  __shared__ float red_s[4];
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int rb = blockIdx.x, lh = blockIdx.y;
+  const int l = lh / a.Hkv, h = lh - l * a.Hkv;
+  int bits = 16, group = 128, n_tok = a.T;
+  const int32_t* list = nullptr;
+  if constexpr (!REFERENCE) {
+    const StreamDesc sd = a.streams[blockIdx.z];
+    bits = sd.bits;
+    group = sd.group;
+    n_tok = a.level_k[sd.level];
+    list = a.level_idx[sd.level];
+    if (list) list += static_cast<int64_t>(lh) * n_tok;
+  }
+  const uint16_t* kbase = a.k + static_cast<int64_t>(l) * a.k_sl + static_cast<int64_t>(h) * a.k_sh;
+  const uint16_t* vbase = a.v + static_cast<int64_t>(l) * a.v_sl + static_cast<int64_t>(h) * a.v_sh;
+  const int win0 = a.T - a.W;
+
+  // stationary operand: this wave's 32 query rows
+  bf16x8 q[8];
+  {
+    const int r = rb * kRowsPerBlock + wave * 32 + (lane & 31);
+    const int half = lane >> 5;
+    if (r < a.M) {
+      const int u = r / a.W, w = r - u * a.W;
+      const uint16_t* row = a.q + static_cast<int64_t>(l) * a.q_sl + static_cast<int64_t>(w) * a.q_st +
+                            static_cast<int64_t>(h * a.G + u) * a.q_sh;
+#pragma unroll
+      for (int ks = 0; ks < 8; ++ks) q[ks] = as_bf16x8(*reinterpret_cast<const uint4*>(row + ks * 16 + half * 8));
+    } else {
+#pragma unroll
+      for (int ks = 0; ks < 8; ++ks) q[ks] = as_bf16x8(make_uint4(0, 0, 0, 0));
+    }
+  }
+  const int qpos = win0 + ((rb * kRowsPerBlock + wave * 32 + (lane & 31)) % a.W);
+  float run_m = -INFINITY, run_z = 0.0f;  // per query (lane%32); run_z is this half-wave's share
+
+  // output tile of this thread: rows {4ty..4ty+3, 64+4ty..}, columns {4tx..4tx+3, 64+4tx..}
+  const int ty = tid >> 4, tx = tid & 15;
+  float o[8][8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i)
+#pragma unroll
+    for (int j = 0; j < 8; ++j) o[i][j] = 0.0f;
+
+  for (int pos0 = 0; pos0 < n_tok; pos0 += kTile) {
+    __syncthreads();  // the previous tile's LDS is no longer read
+    // ---- stage 32 tokens: K-hat (bf16) and V-hat (fp32) ----
+    bool has_window = false;
+#pragma unroll
+    for (int s = 0; s < 2; ++s) {
+      const int slot = tid + s * kThreads;
+      const int tk = slot >> 4, part = slot & 15;
+      const int pos = pos0 + tk;
+      uint4 kraw = make_uint4(0, 0, 0, 0), vraw = make_uint4(0, 0, 0, 0);
+      int t = 0x7fffffff;  // beyond every query position: masked
+      if (pos < n_tok) {
+        t = list ? list[pos] : pos;
+        t = min(max(t, 0), a.T - 1);
+        kraw = *reinterpret_cast<const uint4*>(kbase + static_cast<int64_t>(t) * a.k_st + part * 8);
+        vraw = *reinterpret_cast<const uint4*>(vbase + static_cast<int64_t>(t) * a.v_st + part * 8);
+      }
+      float ky[8], vy[8];
+      fake_quant8(kraw, bits, group, ky);
+      fake_quant8(vraw, bits, group, vy);
+      uint4 kp;
+      kp.x = (__float_as_uint(ky[0]) >> 16) | (__float_as_uint(ky[1]) & 0xffff0000u);
+      kp.y = (__float_as_uint(ky[2]) >> 16) | (__float_as_uint(ky[3]) & 0xffff0000u);
+      kp.z = (__float_as_uint(ky[4]) >> 16) | (__float_as_uint(ky[5]) & 0xffff0000u);
+      kp.w = (__float_as_uint(ky[6]) >> 16) | (__float_as_uint(ky[7]) & 0xffff0000u);
+      *reinterpret_cast<uint4*>(k_s + tk * kPitch + part * 8) = kp;
+      *reinterpret_cast<float4*>(v_s + tk * kHeadDim + part * 8) = make_float4(vy[0], vy[1], vy[2], vy[3]);
+      *reinterpret_cast<float4*>(v_s + tk * kHeadDim + part * 8 + 4) = make_float4(vy[4], vy[5], vy[6], vy[7]);
+      if (part == 0) tok_s[tk] = t;
+      has_window |= (t >= win0);
+    }
+    const bool need_mask = __syncthreads_or(has_window ? 1 : 0) != 0;  // also publishes the stage
+
+    // ---- logits of 32 keys x this wave's 32 queries, online softmax ----
+    {
+      floatx16 acc = {0};
+      const uint16_t* krow = k_s + (lane & 31) * kPitch + (lane >> 5) * 8;
+#pragma unroll
+      for (int ks = 0; ks < 8; ++ks)
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(*reinterpret_cast<const uint4*>(krow + ks * 16)), q[ks],
+                                                      acc, 0, 0, 0);
+      float s[16];
+      float tmax = -INFINITY;
+#pragma unroll
+      for (int vv = 0; vv < 16; ++vv) {
+        s[vv] = acc[vv] * a.scale2;
+        if (need_mask && tok_s[acc_row(lane, vv)] > qpos) s[vv] = -INFINITY;
+        tmax = fmaxf(tmax, s[vv]);
+      }
+      tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
+      const float m_new = fmaxf(run_m, tmax);
+      const float m_safe = (m_new == -INFINITY) ? 0.0f : m_new;
+      const float alpha = __builtin_amdgcn_exp2f(run_m - m_safe);
+      float zsum = 0.0f;
+      const int rloc = wave * 32 + (lane & 31);
+#pragma unroll
+      for (int vv = 0; vv < 16; ++vv) {
+        const float p = __builtin_amdgcn_exp2f(s[vv] - m_safe);
+        zsum += p;
+        p_s[acc_row(lane, vv) * kRowsPerBlock + rloc] = p;
+      }
+      run_z = run_z * alpha + zsum;
+      run_m = m_new;
+      if (lane < 32) alpha_s[rloc] = alpha;
+    }
+    __syncthreads();
+
+    // ---- O = O * alpha + P V on the vector ALU ----
+    {
+      const float4 a0 = *reinterpret_cast<const float4*>(alpha_s + 4 * ty);
+      const float4 a1 = *reinterpret_cast<const float4*>(alpha_s + 64 + 4 * ty);
+      const float al[8] = {a0.x, a0.y, a0.z, a0.w, a1.x, a1.y, a1.z, a1.w};
+#pragma unroll
+      for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int j = 0; j < 8; ++j) o[i][j] *= al[i];
+#pragma unroll 4
+      for (int tk = 0; tk < kTile; ++tk) {
+        const float4 p0 = *reinterpret_cast<const float4*>(p_s + tk * kRowsPerBlock + 4 * ty);
+        const float4 p1 = *reinterpret_cast<const float4*>(p_s + tk * kRowsPerBlock + 64 + 4 * ty);
+        const float4 v0 = *reinterpret_cast<const float4*>(v_s + tk * kHeadDim + 4 * tx);
+        const float4 v1 = *reinterpret_cast<const float4*>(v_s + tk * kHeadDim + 64 + 4 * tx);
+        const float pr[8] = {p0.x, p0.y, p0.z, p0.w, p1.x, p1.y, p1.z, p1.w};
+        const float vc[8] = {v0.x, v0.y, v0.z, v0.w, v1.x, v1.y, v1.z, v1.w};
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+#pragma unroll
+          for (int j = 0; j < 8; ++j) o[i][j] = fmaf(pr[i], vc[j], o[i][j]);
+      }
+    }
+  }
+
+  // ---- normalize, then store (reference) or compare with the reference ----
+  {
+    const float z = run_z + __shfl_xor(run_z, 32, 64);
+    __syncthreads();
+    if (lane < 32) z_s[wave * 32 + lane] = z;
+    __syncthreads();
+  }
+  float sq = 0.0f;
+  float* ofull = a.o_full + (static_cast<int64_t>(lh) * a.RB + rb) * kRowsPerBlock * kHeadDim;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    const int rloc = (i < 4) ? 4 * ty + i : 64 + 4 * ty + (i - 4);
+    const bool live = rb * kRowsPerBlock + rloc < a.M;
+    const float inv = 1.0f / z_s[rloc];
+#pragma unroll
+    for (int jh = 0; jh < 2; ++jh) {
+      const int c0 = jh * 64 + 4 * tx;
+      float4 val = make_float4(o[i][jh * 4 + 0] * inv, o[i][jh * 4 + 1] * inv, o[i][jh * 4 + 2] * inv,
+                               o[i][jh * 4 + 3] * inv);
+      float4* dst = reinterpret_cast<float4*>(ofull + rloc * kHeadDim + c0);
+      if constexpr (REFERENCE) {
+        *dst = val;
+        if (live) sq += val.x * val.x + val.y * val.y + val.z * val.z + val.w * val.w;
+      } else {
+        const float4 ref = *dst;
+        const float dx = val.x - ref.x, dy = val.y - ref.y, dz = val.z - ref.z, dw = val.w - ref.w;
+        if (live) sq += dx * dx + dy * dy + dz * dz + dw * dw;
+      }
+    }
+  }
+  const float total = block_sum(sq, red_s);
+  if (tid == 0) {
+    if constexpr (REFERENCE) {
+      a.den_part[static_cast<int64_t>(lh) * a.RB + rb] = total;
+    } else {
+      a.num_part[(static_cast<int64_t>(lh) * a.RB + rb) * a.n_streams + blockIdx.z] = total;
+    }
+  }
+}
+
+// Fixed-order reduction: thread c owns configuration c.
+__global__ void finish_kernel(const EvalArgs a) {
+  const int c = threadIdx.x;
+  if (c >= a.n_cfgs) return;
+  const int s = a.cfg_stream[c];
+  double num = 0.0, den = 0.0;
+  for (int l = 0; l < a.L; ++l) {
+    double num_l = 0.0, den_l = 0.0;
+    for (int h = 0; h < a.Hkv; ++h)
+      for (int rb = 0; rb < a.RB; ++rb) {
+        const int64_t cell = (static_cast<int64_t>(l) * a.Hkv + h) * a.RB + rb;
+        num_l += static_cast<double>(a.num_part[cell * a.n_streams + s]);
+        den_l += static_cast<double>(a.den_part[cell]);
+      }
+    if (a.partial) {
+      a.partial[(static_cast<int64_t>(l) * a.n_cfgs + c) * 2 + 0] = static_cast<float>(num_l);
+      a.partial[(static_cast<int64_t>(l) * a.n_cfgs + c) * 2 + 1] = static_cast<float>(den_l);
+    }
+    num += num_l;
+    den += den_l;
+  }
+  a.loss[c] = static_cast<float>(sqrt(num / den));
+}
+
+size_t align256(size_t n) { return (n + 255) / 256 * 256; }
+
+struct EvalPlan {
+  int64_t LH, M, RB;
+  size_t score_ws, scores, idx, o_full, den, num, total;
+};
+
+EvalPlan make_plan(int64_t L, int64_t Hkv, int64_t Hq, int64_t W, int64_t T, int32_t n_cfgs) {
+  EvalPlan p{};
+  p.LH = L * Hkv;
+  p.M = (Hq / Hkv) * W;
+  p.RB = ceil_div(p.M, kRowsPerBlock);
+  const int64_t levels = n_cfgs < kMaxLevels ? (n_cfgs > 0 ? n_cfgs : 1) : kMaxLevels;
+  p.score_ws = align256(kvp_score_workspace_bytes(L, Hkv, Hq, W, T));
+  p.scores = align256(static_cast<size_t>(p.LH) * T * sizeof(float));
+  p.idx = align256(static_cast<size_t>(levels) * p.LH * T * sizeof(int32_t));
+  p.o_full = align256(static_cast<size_t>(p.LH) * p.RB * kRowsPerBlock * kHeadDim * sizeof(float));
+  p.den = align256(static_cast<size_t>(p.LH) * p.RB * sizeof(float));
+  p.num = align256(static_cast<size_t>(p.LH) * p.RB * (n_cfgs > 0 ? n_cfgs : 1) * sizeof(float));
+  p.total = p.score_ws + p.scores + p.idx + p.o_full + p.den + p.num;
+  return p;
+}
+
+}  // namespace
+}  // namespace kvp
+
+extern "C" size_t kvp_eval_workspace_bytes(int64_t L, int64_t Hkv, int64_t Hq, int64_t W, int64_t T, int32_t n_cfgs) {
+  if (L <= 0 || Hkv <= 0 || Hq <= 0 || W <= 0 || T <= 0 || Hq % Hkv != 0 || n_cfgs < 0) return 0;
+  return kvp::make_plan(L, Hkv, Hq, W, T, n_cfgs).total;
+}
+
+extern "C" int32_t kvp_eval_configs(const kvp_view* q_win, const kvp_view* k, const kvp_view* v, const kvp_config* cfgs,
+                                    int32_t n_cfgs, float* loss, float* partial, void* ws, size_t ws_bytes,
+                                    void* stream) {
+  using namespace kvp;
+  int32_t rc = check_view(q_win);
+  if (rc != KVP_OK) return rc;
+  rc = check_view(k);
+  if (rc != KVP_OK) return rc;
+  rc = check_view(v);
+  if (rc != KVP_OK) return rc;
+  if (n_cfgs < 0) return KVP_ERR_SHAPE;
+  if (n_cfgs == 0) return KVP_OK;
+  if (!cfgs || !loss) return KVP_ERR_NULL;
+  if (n_cfgs > kMaxCfgs) return KVP_ERR_UNSUPPORTED;
+  const int64_t L = k->L, T = k->T, Hkv = k->H, Hq = q_win->H, W = q_win->T;
+  if (v->L != L || v->T != T || v->H != Hkv || q_win->L != L || Hq % Hkv != 0 || W > T) return KVP_ERR_SHAPE;
+  if (L * Hkv > 65535 || T >= (1ll << 30)) return KVP_ERR_SHAPE;
+
+  EvalArgs a{};
+  // distinct keep levels and distinct (bits, group, level) streams
+  for (int32_t c = 0; c < n_cfgs; ++c) {
+    const kvp_config& cf = cfgs[c];
+    if (cf.bits != 16 && cf.bits != 8 && cf.bits != 4 && cf.bits != 2) return KVP_ERR_UNSUPPORTED;
+    if (cf.bits != 16 && cf.group != 32 && cf.group != 64 && cf.group != 128) return KVP_ERR_UNSUPPORTED;
+    if (cf.keep_k < 1 || cf.keep_k > T) return KVP_ERR_SHAPE;
+    int lev = -1;
+    for (int j = 0; j < a.n_levels; ++j)
+      if (a.level_k[j] == cf.keep_k) lev = j;
+    if (lev < 0) {
+      if (a.n_levels == kMaxLevels) return KVP_ERR_UNSUPPORTED;
+      lev = a.n_levels++;
+      a.level_k[lev] = static_cast<int32_t>(cf.keep_k);
+    }
+    const int32_t grp = cf.bits == 16 ? 128 : cf.group;
+    int s = -1;
+    for (int j = 0; j < a.n_streams; ++j)
+      if (a.streams[j].bits == cf.bits && a.streams[j].group == grp && a.streams[j].level == lev) s = j;
+    if (s < 0) {
+      s = a.n_streams++;
+      a.streams[s] = StreamDesc{cf.bits, grp, lev};
+    }
+    a.cfg_stream[c] = static_cast<uint8_t>(s);
+  }
+
+  const EvalPlan p = make_plan(L, Hkv, Hq, W, T, n_cfgs);
+  if (!ws || ws_bytes < p.total || (reinterpret_cast<uintptr_t>(ws) & 15u)) return KVP_ERR_WORKSPACE;
+  char* base = static_cast<char*>(ws);
+  void* score_ws = base;
+  float* scores = reinterpret_cast<float*>(base + p.score_ws);
+  int32_t* idx = reinterpret_cast<int32_t*>(base + p.score_ws + p.scores);
+  a.o_full = reinterpret_cast<float*>(base + p.score_ws + p.scores + p.idx);
+  a.den_part = reinterpret_cast<float*>(base + p.score_ws + p.scores + p.idx + p.o_full);
+  a.num_part = reinterpret_cast<float*>(base + p.score_ws + p.scores + p.idx + p.o_full + p.den);
+
+  a.q = static_cast<const uint16_t*>(q_win->ptr);
+  a.q_sl = q_win->stride_l; a.q_st = q_win->stride_t; a.q_sh = q_win->stride_h;
+  a.k = static_cast<const uint16_t*>(k->ptr);
+  a.k_sl = k->stride_l; a.k_st = k->stride_t; a.k_sh = k->stride_h;
+  a.v = static_cast<const uint16_t*>(v->ptr);
+  a.v_sl = v->stride_l; a.v_st = v->stride_t; a.v_sh = v->stride_h;
+  a.T = static_cast<int32_t>(T); a.W = static_cast<int32_t>(W); a.G = static_cast<int32_t>(Hq / Hkv);
+  a.Hkv = static_cast<int32_t>(Hkv); a.M = static_cast<int32_t>(p.M); a.RB = static_cast<int32_t>(p.RB);
+  a.L = static_cast<int32_t>(L);
+  a.scale2 = kLog2e / sqrtf(static_cast<float>(kHeadDim));
+  a.n_cfgs = n_cfgs;
+  a.loss = loss;
+  a.partial = partial;
+
+  const hipStream_t st = as_stream(stream);
+  rc = score_tokens_impl(q_win, k, 1, 1, scores, score_ws, p.score_ws, st);
+  if (rc != KVP_OK) return rc;
+  for (int j = 0; j < a.n_levels; ++j) {
+    if (a.level_k[j] == T) {
+      a.level_idx[j] = nullptr;  // all tokens, in order
+    } else {
+      int32_t* out = idx + static_cast<int64_t>(j) * p.LH * T;
+      select_topk_launch(scores, p.LH, T, T, a.level_k[j], out, st);
+      a.level_idx[j] = out;
+    }
+  }
+  attention_kernel<true><<<dim3(static_cast<unsigned>(p.RB), static_cast<unsigned>(p.LH), 1), kThreads, 0, st>>>(a);
+  attention_kernel<false><<<dim3(static_cast<unsigned>(p.RB), static_cast<unsigned>(p.LH),
+                                 static_cast<unsigned>(a.n_streams)), kThreads, 0, st>>>(a);
+  finish_kernel<<<1, kMaxCfgs, 0, st>>>(a);
+  return launch_status();
 }

@@ -8,17 +8,10 @@
 // in registers.  A 256-thread block covers kRowsPerBlock consecutive rows of one layer; all loads of
 // a thread are issued before any arithmetic so that several KiB per wave are in flight.
 //
-// Bit-exact codes without one full IEEE division per element.  The defined result is
-// q = rint(fl32(x / scale)).  The kernel forms y0 = x * rcp(scale) (relative error far below
-// 2^-21), q0 = rint(y0), and accepts q0 whenever y0 is further than kTieMargin from the nearest
-// half-integer: the correctly rounded quotient then lies in the same rounding interval.  Elements
-// that are close to a half-integer are resolved exactly: if fma(-h, scale, x) == 0 the quotient IS
-// the half-integer h (common with bf16 inputs) and rounds to the even neighbour; otherwise the
-// element takes the full IEEE division.  Both slow steps sit behind wave-uniform branches.  For
-// int2 (codes -1, 0, +1, scale = amax) the code is +-1 exactly when 2|x| > amax, which needs no
-// division at all: x / amax is a ratio of two 8-bit significands and cannot round across 1/2.
+// The exact-code arithmetic (reciprocal fast path with an exact fallback) lives in quant_device.h.
 
 #include "kvp_common.h"
+#include "quant_device.h"
 
 namespace kvp {
 namespace {
@@ -46,22 +39,6 @@ struct QuantArgs {
   float* scales;
 };
 
-template <int CTRL>
-__device__ __forceinline__ float dpp_max(float v) {
-  const int moved = __builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, true);
-  return fmaxf(v, __int_as_float(moved));
-}
-
-// abs-max over the LANES adjacent lanes (4, 8 or 16) that share a group.
-template <int LANES>
-__device__ __forceinline__ float group_max(float v) {
-  v = dpp_max<0xB1>(v);                       // quad_perm [1,0,3,2]
-  v = dpp_max<0x4E>(v);                       // quad_perm [2,3,0,1]
-  if (LANES >= 8) v = dpp_max<0x141>(v);      // row_half_mirror: quads 0<->1, 2<->3
-  if (LANES >= 16) v = dpp_max<0x140>(v);     // row_mirror: halves of the 16-lane row
-  return v;
-}
-
 template <int BITS>
 struct Packed;  // the 8 codes of one lane
 template <> struct Packed<8> { uint32_t lo, hi; };
@@ -83,67 +60,25 @@ __device__ __forceinline__ void store_codes<2>(uint8_t* row_codes, int lane_in_r
   *reinterpret_cast<uint16_t*>(row_codes + lane_in_row * 2) = static_cast<uint16_t>(p.w);
 }
 
-// Code of one element, bit-exact with rint(fl32(x / scale)); see the file header.
-template <int QMAX>
-__device__ __forceinline__ int exact_code(float x, float scale, float inv, bool unsafe) {
-  // |y0 - fl32(x/scale)| <= |x/scale| * (2^-22 + 2^-24 + 2^-24) < (QMAX + 1) * 2^-21
-  constexpr float kTieMargin = static_cast<float>(QMAX + 1) * 0x1p-20f;
-  const float y0 = x * inv;
-  float q0 = rintf(y0);
-  const float d = y0 - q0;  // exact
-  const bool risky = unsafe || fabsf(d) > 0.5f - kTieMargin;
-  if (__builtin_amdgcn_ballot_w64(risky)) {
-    if (risky) {
-      const float h = q0 + copysignf(0.5f, d);      // nearest half-integer, exact
-      const float e = fmaf(-h, scale, x);           // zero exactly when x / scale == h
-      const bool divide = unsafe || e != 0.0f;
-      if (!divide) q0 = rintf(h);
-      if (__builtin_amdgcn_ballot_w64(divide)) {
-        if (divide) q0 = rintf(x / scale);
-      }
-    }
-  }
-  return static_cast<int>(q0);
-}
-
 template <int BITS, int GROUP>
 __device__ __forceinline__ void quantize_lane(const uint4 raw, Packed<BITS>& out, float& scale_out) {
   constexpr int QMAX = (1 << (BITS - 1)) - 1;
-  const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
   float x[8];
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    x[2 * i] = bf16lo(w[i]);
-    x[2 * i + 1] = bf16hi(w[i]);
-  }
-  float amax = 0.0f;
-#pragma unroll
-  for (int i = 0; i < 8; ++i) amax = fmaxf(amax, fabsf(x[i]));
-  amax = group_max<GROUP / 8>(amax);
+  unpack_bf16x8(raw, x);
+  const float amax = group_max(abs_max8(x), GROUP / 8);
 
   if constexpr (BITS == 2) {
     scale_out = amax;  // qmax = 1
     uint32_t word = 0;
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      const bool nz = 2.0f * fabsf(x[i]) > amax;               // doubling is exact
-      const uint32_t field = nz ? (x[i] < 0.0f ? 3u : 1u) : 0u;
-      word |= field << (2 * i);
-    }
+    for (int i = 0; i < 8; ++i) word |= static_cast<uint32_t>(ternary_code(x[i], amax) & 3) << (2 * i);
     out.w = word;
   } else {
-    const float scale = amax / static_cast<float>(QMAX);       // IEEE division
-    scale_out = scale;
-    // outside this range rcp or the products may leave the normal range: take the division path
-    const bool unsafe = !(scale >= 0x1p-100f && scale <= 0x1p100f) && scale != 0.0f;
-    const float inv = (scale == 0.0f) ? 0.0f : __builtin_amdgcn_rcpf(scale);
+    const GroupScale<QMAX> gs(amax);
+    scale_out = gs.scale;
     int q[8];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      int v = exact_code<QMAX>(x[i], scale, inv, unsafe);
-      v = min(QMAX, max(-QMAX, v));
-      q[i] = v;
-    }
+    for (int i = 0; i < 8; ++i) q[i] = gs.code(x[i]);
     if constexpr (BITS == 8) {
       out.lo = (q[0] & 0xff) | ((q[1] & 0xff) << 8) | ((q[2] & 0xff) << 16) | (static_cast<uint32_t>(q[3]) << 24);
       out.hi = (q[4] & 0xff) | ((q[5] & 0xff) << 8) | ((q[6] & 0xff) << 16) | (static_cast<uint32_t>(q[7]) << 24);

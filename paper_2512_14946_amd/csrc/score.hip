@@ -25,7 +25,7 @@
 //          lane-private adds plus one exchange between half-waves and a 4-way sum across waves in LDS.
 // Every key chunk is owned by exactly one block: no atomics, deterministic output.
 
-#include "kvp_common.h"
+#include "kvp_internal.h"
 
 namespace kvp {
 namespace {

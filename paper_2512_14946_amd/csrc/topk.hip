@@ -13,7 +13,7 @@
 // The row is re-read from global memory in every pass; after the first pass it is served by L2
 // (a row is at most 512 KiB at T = 131072).
 
-#include "kvp_common.h"
+#include "kvp_internal.h"
 
 namespace kvp {
 namespace {
@@ -176,6 +176,12 @@ __global__ __launch_bounds__(kThreads) void select_topk_kernel(const float* __re
 }
 
 }  // namespace
+
+void select_topk_launch(const float* scores, int64_t n_rows, int64_t T, int64_t row_stride, int64_t k,
+                        int32_t* idx_out, hipStream_t st) {
+  select_topk_kernel<<<dim3(static_cast<unsigned>(n_rows)), kThreads, 0, st>>>(scores, T, row_stride, k, idx_out);
+}
+
 }  // namespace kvp
 
 extern "C" size_t kvp_select_workspace_bytes(int64_t, int64_t, int64_t) { return 0; }
@@ -190,7 +196,6 @@ extern "C" int32_t kvp_select_topk(const float* scores, int64_t n_rows, int64_t 
     return KVP_ERR_SHAPE;
   if ((reinterpret_cast<uintptr_t>(scores) & 3u) || (reinterpret_cast<uintptr_t>(idx_out) & 3u)) return KVP_ERR_ALIGN;
   if (n_rows == 0 || k == 0) return KVP_OK;
-  select_topk_kernel<<<dim3(static_cast<unsigned>(n_rows)), kThreads, 0, as_stream(stream)>>>(scores, T, row_stride,
-                                                                                               k, idx_out);
+  select_topk_launch(scores, n_rows, T, row_stride, k, idx_out, as_stream(stream));
   return launch_status();
 }

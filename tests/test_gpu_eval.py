@@ -1,0 +1,74 @@
+"""GPU parity: kvp_eval_configs against the CPU oracle (1e-2 relative + 1e-5 absolute)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import workloads
+from helpers import torch_bits
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def _kvp():
+    import paper_2512_14946_amd as kvp
+    return kvp
+
+
+def _case(L, W, G, H, T, cfgs, seed, outlier=8.0):
+    kvp = _kvp()
+    D = 128
+    print("[case] eval", dict(L=L, W=W, G=G, H=H, T=T, n=len(cfgs)), flush=True)
+    K, V = workloads.make_kv(L, T, H, D, seed=seed, outlier_scale=outlier)
+    Q = workloads.make_q(L, W, G * H, D, seed=seed)
+    loss, partial = kvp.kvp_eval_configs(Q.to(DEV), K.to(DEV), V.to(DEV), cfgs, want_partial=True)
+    torch.cuda.synchronize()
+    loss, partial = loss.cpu().numpy(), partial.cpu().numpy()
+    ref, ref_partial = oracle.eval_configs(torch_bits(Q), torch_bits(K), torch_bits(V), cfgs)
+    assert np.all(np.abs(loss - ref) <= 1e-2 * np.abs(ref) + 1e-5), (loss, ref)
+    assert np.allclose(partial[..., 1], ref_partial[..., 1], rtol=1e-3)
+    assert np.all(np.abs(partial[..., 0] - ref_partial[..., 0]) <= 3e-2 * ref_partial[..., 0] + 1e-7)
+    return loss, ref
+
+
+def _sweep(T):
+    ks = [oracle.keep_count(r, T) for r in (0.25, 0.5, 0.75)] + [T]
+    variants = [(16, 0)] + [(b, g) for b in (8, 4, 2) for g in (32, 64, 128)]
+    return [(b, g, k) for (b, g) in variants for k in ks]
+
+
+def test_full_candidate_sweep_small():
+    T = 300                                            # ragged: 300 = 9 tiles of 32 + 12
+    cfgs = _sweep(T)
+    assert len(cfgs) == 40
+    loss, ref = _case(2, 32, 4, 2, T, cfgs, seed=0)
+    assert loss[3] == 0.0                              # (16 bits, keep all) is the identity, exactly
+    order = {c: i for i, c in enumerate(cfgs)}
+    for g in (32, 64, 128):                            # fewer bits, larger loss
+        assert loss[order[(8, g, T)]] < loss[order[(4, g, T)]] < loss[order[(2, g, T)]]
+
+
+def test_padded_row_blocks_and_tiny_keep():
+    T = 200
+    cfgs = [(16, 0, T), (8, 128, T), (4, 32, 77), (2, 64, 33), (16, 0, 5), (4, 64, 1)]
+    _case(1, 32, 7, 2, T, cfgs, seed=1, outlier=16.0)  # M = 224: two row blocks, the second partly filled
+
+
+def test_many_rows_and_duplicates():
+    T = 130
+    cfgs = [(8, 32, 64), (8, 32, 64), (16, 0, 64), (2, 32, T)]
+    loss, _ = _case(1, 64, 8, 1, T, cfgs, seed=2)      # M = 512: four row blocks
+    assert loss[0] == loss[1]
+
+
+def test_errors():
+    kvp = _kvp()
+    q = torch.zeros(1, 8, 4, 128, dtype=torch.bfloat16, device=DEV)
+    k = torch.zeros(1, 64, 2, 128, dtype=torch.bfloat16, device=DEV)
+    with pytest.raises(kvp.KVPError):
+        kvp.kvp_eval_configs(q, k, k, [(3, 32, 64)])
+    with pytest.raises(kvp.KVPError):
+        kvp.kvp_eval_configs(q, k, k, [(4, 32, 65)])
+    with pytest.raises(kvp.KVPError):
+        kvp.kvp_eval_configs(q, k, k, [(4, 32, 8)], ws=torch.empty(16, dtype=torch.uint8, device=DEV))
