@@ -1,0 +1,338 @@
+#!/usr/bin/env python3
+"""Throughput benchmark of the KV compress + decompress hot path on one MI355X.
+
+A step = kvp_quantize(K), kvp_quantize(V), kvp_dequantize_paged(K), kvp_dequantize_paged(V) on the
+Llama-3-8B-shaped cache (32 layers x 8 KV heads x 128 x 32768 tokens, bf16, int4 group 64, 16-token
+pages, scattered block table), inputs resident in HBM.  value = input KV bytes (K+V, bf16) per
+second over the timed steps.  The same JSON line carries the roofline of the dominant kernel
+(measured with HIP events on the launch stream inside the timed region), the CPU oracle timed on a
+bounded sample, and per-operation figures for the other entry points on their own workloads.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import re
+import sys
+import time
+from concurrent.futures import ThreadPoolExecutor
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16
+VALU_FP32_PEAK_TFLOPS = 78.6    # 256 CU x 4 SIMD x 16 lanes x 2 flop x 2.4 GHz, no packed fp32
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--layers", type=int, default=None, help="override the layer count (debugging only)")
+    ap.add_argument("--no-ops", action="store_true", help="skip the per-operation side measurements")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--only", default=None,
+                    help="profiling aid: run only one operation in a loop (quantize|dequantize|copy|score|select|eval)")
+    return ap.parse_args()
+
+
+def ensure_built():
+    from paper_2512_14946_amd import build
+    if not os.path.exists(build.LIB):
+        build.build_library()
+
+
+def event_ms(pairs):
+    return [a.elapsed_time(b) for a, b in pairs]
+
+
+def traffic_from_profiles(name: str):
+    """HBM bytes per launch measured offline with rocprofv3 --pmc, if the summary is committed."""
+    path = os.path.join(ROOT, "profiles", name)
+    if not os.path.exists(path):
+        return None
+    m = re.search(r"traffic_bytes_per_launch:\s*([0-9.eE+]+)", open(path).read())
+    return float(m.group(1)) if m else None
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (every box here has one); --gpus N with N > 1 is not "
+              "supported. The path shards by context / layer / KV head with no exchange (see DESIGN.md).",
+              file=sys.stderr)
+        sys.exit(2)
+    ensure_built()
+    import torch
+    import paper_2512_14946_amd as kvp
+    import workloads
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the kvp_* operations have no CPU fallback", file=sys.stderr)
+        sys.exit(2)
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    stream = torch.cuda.current_stream()
+
+    cfg = dict(workloads.CONFIGS["llama3_8b_int4_paged"])
+    if args.layers:
+        cfg["L"] = args.layers
+    L, T, H, D, bits, group, bs = cfg["L"], cfg["T"], cfg["H"], cfg["D"], cfg["bits"], cfg["group"], cfg["bs"]
+    K, V = workloads.make_kv(L, T, H, D, seed=0, outlier_scale=cfg["outlier_scale"], device=dev)
+    bt, nb = workloads.make_block_table(T, bs, seed=0, device=dev)
+    qK = kvp.alloc_qplane(L, T, H, D, bits, group, dev, page=bs)
+    qV = kvp.alloc_qplane(L, T, H, D, bits, group, dev, page=bs)
+    pK = kvp.alloc_paged(L, T, H, D, bt, nb, bs)
+    pV = kvp.alloc_paged(L, T, H, D, bt, nb, bs)
+    plane_bytes = K.numel() * 2
+    input_bytes = 2 * plane_bytes
+    comp_bytes = qK.nbytes()
+    alg_bytes_per_launch = plane_bytes + comp_bytes   # one quantize (or dequantize) launch over one plane
+
+    def ev():
+        return torch.cuda.Event(enable_timing=True)
+
+    if args.only:
+        return profile_only(args, kvp, workloads, torch, dev, K, V, qK, pK, bt, nb)
+
+    def step(marks=None):
+        if marks is not None:
+            e = [ev() for _ in range(5)]
+            e[0].record(stream)
+        kvp.kvp_quantize(K, qK)
+        if marks is not None:
+            e[1].record(stream)
+        kvp.kvp_quantize(V, qV)
+        if marks is not None:
+            e[2].record(stream)
+        kvp.kvp_dequantize_paged(qK, pK)
+        if marks is not None:
+            e[3].record(stream)
+        kvp.kvp_dequantize_paged(qV, pV)
+        if marks is not None:
+            e[4].record(stream)
+            marks.append(e)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    marks = []
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step(marks)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = wall * 1e3 / args.steps
+    value = input_bytes / (wall / args.steps) / 1e9
+
+    q_ms = [m for e in marks for m in event_ms([(e[0], e[1]), (e[1], e[2])])]
+    d_ms = [m for e in marks for m in event_ms([(e[2], e[3]), (e[3], e[4])])]
+    q_avg, d_avg = sum(q_ms) / len(q_ms), sum(d_ms) / len(d_ms)
+    achieved = alg_bytes_per_launch / (q_avg * 1e-3) / 1e9
+    roofline = {
+        "bound": "hbm", "kernel": f"quantize_kernel<{bits},{group},linear>", "achieved": round(achieved, 1),
+        "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
+        "traffic": traffic_from_profiles("quantize_int4g64_llama3_8b_pmc.md"),
+        "algorithmic_bytes_per_launch": alg_bytes_per_launch, "avg_launch_ms": round(q_avg, 4),
+        "dequantize": {"kernel": f"dequantize_paged_kernel<{bits},{group}>", "avg_launch_ms": round(d_avg, 4),
+                       "achieved": round(alg_bytes_per_launch / (d_avg * 1e-3) / 1e9, 1),
+                       "frac": round(alg_bytes_per_launch / (d_avg * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)},
+    }
+
+    # plain copy of the same plane: the practical ceiling of a streaming kernel on this part
+    tmp = torch.empty_like(K)
+    for _ in range(2):
+        kvp.kvp_copy_bytes(tmp, K)
+    a, b = ev(), ev()
+    a.record(stream)
+    for _ in range(10):
+        kvp.kvp_copy_bytes(tmp, K)
+    b.record(stream)
+    torch.cuda.synchronize()
+    copy_gbs = 2 * plane_bytes / (a.elapsed_time(b) / 10 * 1e-3) / 1e9
+    roofline["copy_kernel_GBs"] = round(copy_gbs, 1)
+    roofline["frac_of_copy"] = round(achieved / copy_gbs, 4)
+    del tmp
+
+    cpu = None
+    if not args.no_cpu:
+        cpu = cpu_baseline(K, V, bt, nb, cfg)
+
+    ops = None
+    if not args.no_ops:
+        del qK, qV, pK, pV
+        torch.cuda.empty_cache()
+        ops = side_measurements(kvp, workloads, torch, dev, K, V)
+
+    out = {
+        "metric": "KV compress+decompress GB/s (input KV bytes), 1 GPU",
+        "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "llama3_8b_int4_paged", "shape": f"{L}x{H}x{D}x{T} bf16 K and V",
+                   "codec": f"int{bits} group {group}", "page_tokens": bs, "input_bytes": input_bytes,
+                   "step": "quantize(K), quantize(V), dequantize_paged(K), dequantize_paged(V)"},
+        "pct_of_hbm_peak_per_op": {"quantize": round(100 * roofline["frac"], 1),
+                                   "dequantize": round(100 * roofline["dequantize"]["frac"], 1)},
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+        "ops": ops,
+    }
+    print(json.dumps(out))
+
+
+def cpu_baseline(K, V, bt, nb, cfg):
+    """The CPU oracle, as it stands, on a bounded sample of the same workload (layers split over threads)."""
+    import numpy as np
+    import oracle
+    oracle.build()
+    sample_layers = min(8, K.shape[0])
+    cores = min(os.cpu_count() or 1, 16)
+    T, bs, bits, group = cfg["T"], cfg["bs"], cfg["bits"], cfg["group"]
+    kb = K[:sample_layers].cpu().view(__import__("torch").int16).numpy().view(np.uint16)
+    vb = V[:sample_layers].cpu().view(__import__("torch").int16).numpy().view(np.uint16)
+    btn = bt.cpu().numpy()
+    # split every layer in token slabs so that all threads have work; each slab is a whole number of pages
+    slabs = max(1, cores * 2 // sample_layers)
+    slab_tokens = (T // slabs) // bs * bs
+    jobs = []
+    for plane in (kb, vb):
+        for l in range(sample_layers):
+            for s in range(slabs):
+                t0 = s * slab_tokens
+                t1 = T if s == slabs - 1 else t0 + slab_tokens
+                jobs.append((plane, l, t0, t1))
+
+    def run(job):
+        plane, l, t0, t1 = job
+        x = plane[l:l + 1, t0:t1]
+        codes, scales = oracle.quantize(x, bits, group)
+        n = t1 - t0
+        oracle.dequantize_paged(codes, scales, bits, group, n, np.arange((n + bs - 1) // bs, dtype=np.int32),
+                                (n + bs - 1) // bs, bs)
+        return x.nbytes
+
+    t0 = time.perf_counter()
+    with ThreadPoolExecutor(max_workers=cores) as ex:
+        done = sum(ex.map(run, jobs))
+    dt = time.perf_counter() - t0
+    return {"value": round(done / dt / 1e9, 3), "unit": "GB/s", "cores": cores, "kind": "oracle",
+            "sample": f"{sample_layers} of {K.shape[0]} layers of the same K and V ({done / 2**20:.0f} MiB of input), "
+                      f"quantize + dequantize_paged, {len(jobs)} token slabs over {cores} threads",
+            "seconds": round(dt, 2)}
+
+
+def _time_loop(torch, fn, iters, warm=1):
+    for _ in range(warm):
+        fn()
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    for _ in range(iters):
+        fn()
+    b.record()
+    torch.cuda.synchronize()
+    return a.elapsed_time(b) / iters * 1e-3
+
+
+def side_measurements(kvp, workloads, torch, dev, K8, V8):
+    """Per-operation figures on the other benchmark configurations (outside the timed steps)."""
+    ops = {}
+    # --- int8 g128 and int2 g32 codecs on the resident 8B-shaped planes (beyond the last-level cache) ---
+    L, T, H, D = K8.shape
+    bt, nb = workloads.make_block_table(T, 16, seed=0, device=dev)
+    for name, bits, group in [("int8_g128", 8, 128), ("int2_g32", 2, 32), ("int4_g32", 4, 32)]:
+        qp = kvp.alloc_qplane(L, T, H, D, bits, group, dev)
+        pg = kvp.alloc_paged(L, T, H, D, bt, nb, 16)
+        tq = _time_loop(torch, lambda: kvp.kvp_quantize(K8, qp), 5)
+        td = _time_loop(torch, lambda: kvp.kvp_dequantize_paged(qp, pg), 5)
+        alg = K8.numel() * 2 + qp.nbytes()
+        ops[name] = {"workload": f"{L}x{H}x{D}x{T} plane", "quantize_GBs_alg": round(alg / tq / 1e9, 1),
+                     "dequantize_GBs_alg": round(alg / td / 1e9, 1),
+                     "quantize_frac_hbm": round(alg / tq / 1e9 / HBM_PEAK_GBS, 4),
+                     "dequantize_frac_hbm": round(alg / td / 1e9 / HBM_PEAK_GBS, 4)}
+        del qp, pg
+    # --- 70B-shaped drop + quantize pipeline on a 16-layer slice of the resident planes' shape ---
+    c = workloads.CONFIGS["llama3_70b_drop_int4"]
+    Ls = 16
+    Kc, Vc = workloads.make_kv(Ls, c["T"], c["H"], c["D"], seed=0, device=dev)
+    Qc = workloads.make_q(Ls, c["W"], c["G"] * c["H"], c["D"], seed=0, device=dev)
+    k = kvp.kvp_keep_count(c["keep_ratio"], c["T"])
+    sc = torch.empty(Ls, c["H"], c["T"], dtype=torch.float32, device=dev)
+    ws = torch.empty(kvp.kvp_score_workspace_bytes(Ls, c["H"], c["G"] * c["H"], c["W"], c["T"]) + 16,
+                     dtype=torch.uint8, device=dev)
+    idx = torch.empty(Ls * c["H"], k, dtype=torch.int32, device=dev)
+    qk = kvp.alloc_qplane(Ls, k, c["H"], c["D"], c["bits"], c["group"], dev)
+    t_score = _time_loop(torch, lambda: kvp.kvp_score_tokens(Qc, Kc, sc, ws=ws), 5)
+    t_sel = _time_loop(torch, lambda: kvp.kvp_select_topk(sc.view(Ls * c["H"], c["T"]), k, idx), 10)
+    keep = idx.view(Ls, c["H"], k)
+    t_gq = _time_loop(torch, lambda: kvp.kvp_quantize(Kc, qk, keep_idx=keep), 5)
+    M = c["G"] * c["W"]
+    flops = 2 * 2.0 * Ls * c["H"] * M * c["T"] * c["D"]
+    sel_bytes = Ls * c["H"] * (c["T"] + k) * 4
+    gq_bytes = Ls * k * c["H"] * c["D"] * 2 + qk.nbytes() + idx.numel() * 4
+    ops["llama3_70b_drop_int4"] = {
+        "workload": f"{Ls} of 80 layers x {c['H']} x {c['D']} x {c['T']}, G={c['G']}, W={c['W']}, keep {k}",
+        "score_ms": round(t_score * 1e3, 3), "score_TFLOPs": round(flops / t_score / 1e12, 1),
+        "score_frac_mfma": round(flops / t_score / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
+        "select_us": round(t_sel * 1e6, 1), "select_GBs_alg": round(sel_bytes / t_sel / 1e9, 1),
+        "select_frac_hbm": round(sel_bytes / t_sel / 1e9 / HBM_PEAK_GBS, 4),
+        "gather_quantize_ms_per_plane": round(t_gq * 1e3, 3), "gather_quantize_GBs_alg": round(gq_bytes / t_gq / 1e9, 1),
+        "pipeline_input_GBs": round(2 * Kc.numel() * 2 / (t_score + t_sel + 2 * t_gq) / 1e9, 1)}
+    del Kc, Vc, Qc, sc, ws, idx, qk
+    # --- long-context select: 112 rows of 131072 scores ---
+    c = workloads.CONFIGS["long_context_int2"]
+    rows = c["L"] * c["H"]
+    k = kvp.kvp_keep_count(c["keep_ratio"], c["T"])
+    s = workloads.make_scores(rows, c["T"], seed=0, device=dev)
+    idx = torch.empty(rows, k, dtype=torch.int32, device=dev)
+    t_sel = _time_loop(torch, lambda: kvp.kvp_select_topk(s, k, idx), 10)
+    ops["long_context_select"] = {"workload": f"{rows} rows x {c['T']} squared-normal stand-in scores, k={k}",
+                                  "select_us": round(t_sel * 1e6, 1),
+                                  "select_GBs_alg": round(rows * (c["T"] + k) * 4 / t_sel / 1e9, 1)}
+    del s, idx
+    # --- utility-table sweep: one context of the 64 ---
+    c = workloads.CONFIGS["utility_sweep"]
+    Ke, Ve = workloads.make_kv(c["L"], c["T"], c["H"], c["D"], seed=0, device=dev)
+    Qe = workloads.make_q(c["L"], c["W"], c["G"] * c["H"], c["D"], seed=0, device=dev)
+    ks = [kvp.kvp_keep_count(r, c["T"]) for r in c["keep_ratios"]] + [c["T"]]
+    variants = [(16, 0)] + [(b, g) for b in c["bits_set"] for g in c["group_set"]]
+    cfgs = [(b, g, kk) for (b, g) in variants for kk in ks]
+    ws = torch.empty(kvp.kvp_eval_workspace_bytes(c["L"], c["H"], c["G"] * c["H"], c["W"], c["T"], len(cfgs)),
+                     dtype=torch.uint8, device=dev)
+    loss = torch.empty(len(cfgs), dtype=torch.float32, device=dev)
+    t_ev = _time_loop(torch, lambda: kvp.kvp_eval_configs(Qe, Ke, Ve, cfgs, loss=loss, ws=ws), 2)
+    M = c["G"] * c["W"]
+    tokens = sum(kk for (_, _, kk) in cfgs)
+    pv_flops = 2.0 * c["L"] * c["H"] * M * c["D"] * tokens
+    ops["utility_sweep"] = {"workload": f"1 of {c['n_ctx']} contexts: {c['L']}x{c['H']}x{c['D']}x{c['T']}, {len(cfgs)} configs",
+                            "eval_ms_per_context": round(t_ev * 1e3, 2), "configs_per_s": round(len(cfgs) / t_ev, 1),
+                            "bound": "alu", "pv_TFLOPs_fp32": round(pv_flops / t_ev / 1e12, 2),
+                            "pv_frac_valu_peak": round(pv_flops / t_ev / 1e12 / VALU_FP32_PEAK_TFLOPS, 4)}
+    return ops
+
+
+def profile_only(args, kvp, workloads, torch, dev, K, V, qK, pK, bt, nb):
+    """Loop one operation so that a profiler sees only it (used for the summaries under profiles/)."""
+    n = args.steps
+    if args.only == "quantize":
+        for _ in range(n):
+            kvp.kvp_quantize(K, qK)
+    elif args.only == "dequantize":
+        kvp.kvp_quantize(K, qK)
+        for _ in range(n):
+            kvp.kvp_dequantize_paged(qK, pK)
+    elif args.only == "copy":
+        tmp = torch.empty_like(K)
+        for _ in range(n):
+            kvp.kvp_copy_bytes(tmp, K)
+    else:
+        raise SystemExit(f"unknown --only {args.only}")
+    torch.cuda.synchronize()
+    print(json.dumps({"only": args.only, "launches": n, "plane_bytes": K.numel() * 2, "compressed_bytes": qK.nbytes()}))
+
+
+if __name__ == "__main__":
+    main()
