@@ -189,7 +189,7 @@ def cpu_baseline(K, V, bt, nb, cfg):
     import numpy as np
     import oracle
     oracle.build()
-    sample_layers = min(8, K.shape[0])
+    sample_layers = min(32, K.shape[0])
     cores = min(os.cpu_count() or 1, 16)
     T, bs, bits, group = cfg["T"], cfg["bs"], cfg["bits"], cfg["group"]
     kb = K[:sample_layers].cpu().view(__import__("torch").int16).numpy().view(np.uint16)

@@ -86,19 +86,22 @@ __device__ __forceinline__ void fake_quant8(const uint4 raw, int bits, int group
     return;
   }
   const float amax = group_max(abs_max8(x), group / 8);
+  float q[8];
   if (bits == 2) {
+    const TernaryQuantizer tq(amax);
+    tq.codes8(x, q);
 #pragma unroll
-    for (int i = 0; i < 8; ++i) y[i] = static_cast<float>(ternary_code(x[i], amax)) * amax;
+    for (int i = 0; i < 8; ++i) y[i] = q[i] * amax;   // +-amax or 0: already a bf16 value
   } else if (bits == 4) {
-    const GroupScale<7> gs(amax);
+    const GroupQuantizer<7> gq(amax);
+    gq.codes8(x, q);
 #pragma unroll
-    for (int i = 0; i < 8; ++i)
-      y[i] = __uint_as_float(f32_to_bf16_bits(static_cast<float>(gs.code(x[i])) * gs.scale) << 16);
+    for (int i = 0; i < 8; ++i) y[i] = __uint_as_float(f32_to_bf16_bits(q[i] * gq.scale) << 16);
   } else {
-    const GroupScale<127> gs(amax);
+    const GroupQuantizer<127> gq(amax);
+    gq.codes8(x, q);
 #pragma unroll
-    for (int i = 0; i < 8; ++i)
-      y[i] = __uint_as_float(f32_to_bf16_bits(static_cast<float>(gs.code(x[i])) * gs.scale) << 16);
+    for (int i = 0; i < 8; ++i) y[i] = __uint_as_float(f32_to_bf16_bits(q[i] * gq.scale) << 16);
   }
 }
 

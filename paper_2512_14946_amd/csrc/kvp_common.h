@@ -60,6 +60,42 @@ inline int32_t check_qplane(const kvp_qplane* q) {
   return KVP_OK;
 }
 
+// ---- streaming (non-temporal) global accesses ------------------------------------------------
+// K/V planes are read once and written once per call; marking the accesses non-temporal keeps them
+// from displacing each other in the caches and measurably raises the sustained HBM rate.
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ uint4 load_stream16(const void* p) {
+  const u32x4_t v = __builtin_nontemporal_load(static_cast<const u32x4_t*>(p));
+  return make_uint4(v.x, v.y, v.z, v.w);
+}
+__device__ __forceinline__ uint2 load_stream8(const void* p) {
+  const u32x2_t v = __builtin_nontemporal_load(static_cast<const u32x2_t*>(p));
+  return make_uint2(v.x, v.y);
+}
+__device__ __forceinline__ uint32_t load_stream4(const void* p) {
+  return __builtin_nontemporal_load(static_cast<const uint32_t*>(p));
+}
+__device__ __forceinline__ uint32_t load_stream2(const void* p) {
+  return __builtin_nontemporal_load(static_cast<const uint16_t*>(p));
+}
+__device__ __forceinline__ void store_stream16(void* p, uint4 v) {
+  const u32x4_t w = {v.x, v.y, v.z, v.w};
+  __builtin_nontemporal_store(w, static_cast<u32x4_t*>(p));
+}
+__device__ __forceinline__ void store_stream8(void* p, uint2 v) {
+  const u32x2_t w = {v.x, v.y};
+  __builtin_nontemporal_store(w, static_cast<u32x2_t*>(p));
+}
+__device__ __forceinline__ void store_stream4(void* p, uint32_t v) {
+  __builtin_nontemporal_store(v, static_cast<uint32_t*>(p));
+}
+__device__ __forceinline__ void store_stream2(void* p, uint32_t v) {
+  __builtin_nontemporal_store(static_cast<uint16_t>(v), static_cast<uint16_t*>(p));
+}
+__device__ __forceinline__ void store_stream_f32(float* p, float v) { __builtin_nontemporal_store(v, p); }
+
 // ---- device-side bf16 helpers ------------------------------------------------------------
 
 // Two bf16 packed in one 32-bit word -> two floats (exact).
@@ -73,8 +109,15 @@ __device__ __forceinline__ uint32_t f32_to_bf16_bits(float f) {
   u += 0x7fffu + ((u >> 16) & 1u);
   return u >> 16;
 }
+// Two floats -> two bf16 in one word with the gfx950 packed convert (v_cvt_pk_bf16_f32; the
+// compiler emits it for this vector fptrunc, whose semantics are round-to-nearest-even).
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef float floatx2_t __attribute__((ext_vector_type(2)));
 __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
-  return f32_to_bf16_bits(lo) | (f32_to_bf16_bits(hi) << 16);
+  const floatx2_t f = {lo, hi};
+  union { bf16x2_t b; uint32_t u; } c;
+  c.b = __builtin_convertvector(f, bf16x2_t);
+  return c.u;
 }
 
 }  // namespace kvp

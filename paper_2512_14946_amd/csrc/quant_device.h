@@ -2,7 +2,7 @@
 // configuration-evaluation kernels (which quantize and dequantize on the fly).
 //
 // Bit-exact codes without one full IEEE division per element.  The defined result is
-// q = rint(fl32(x / scale)).  exact_code() forms y0 = x * rcp(scale) (relative error far below
+// q = rint(fl32(x / scale)).  GroupQuantizer::code() forms y0 = x * rcp(scale) (relative error far below
 // 2^-21), q0 = rint(y0), and accepts q0 whenever y0 is further than kTieMargin from the nearest
 // half-integer: the correctly rounded quotient then lies in the same rounding interval.  Elements
 // close to a half-integer are resolved exactly: if fma(-h, scale, x) == 0 the quotient IS the
@@ -14,67 +14,107 @@
 
 namespace kvp {
 
+// Cross-lane max of non-negative floats, taken on their bit patterns as unsigned integers (the IEEE
+// order of non-negative floats is the order of their patterns), so that no NaN canonicalization is
+// emitted and the DPP operand folds into the max instruction.
 template <int CTRL>
-__device__ __forceinline__ float dpp_max(float v) {
-  const int moved = __builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, true);
-  return fmaxf(v, __int_as_float(moved));
+__device__ __forceinline__ uint32_t dpp_umax(uint32_t v) {
+  const uint32_t moved = static_cast<uint32_t>(__builtin_amdgcn_update_dpp(0, static_cast<int>(v), CTRL, 0xf, 0xf, true));
+  return max(v, moved);
 }
 
 // max over the `lanes` adjacent lanes (4, 8 or 16, aligned) that share a quantization group;
-// `lanes` must be uniform across the wave.
+// `lanes` must be uniform across the wave and v must be non-negative.
 __device__ __forceinline__ float group_max(float v, int lanes) {
-  v = dpp_max<0xB1>(v);                      // quad_perm [1,0,3,2]
-  v = dpp_max<0x4E>(v);                      // quad_perm [2,3,0,1]
-  if (lanes >= 8) v = dpp_max<0x141>(v);     // row_half_mirror: quads 0<->1, 2<->3
-  if (lanes >= 16) v = dpp_max<0x140>(v);    // row_mirror: halves of the 16-lane row
-  return v;
+  uint32_t u = __float_as_uint(v);
+  u = dpp_umax<0xB1>(u);                     // quad_perm [1,0,3,2]
+  u = dpp_umax<0x4E>(u);                     // quad_perm [2,3,0,1]
+  if (lanes >= 8) u = dpp_umax<0x141>(u);    // row_half_mirror: quads 0<->1, 2<->3
+  if (lanes >= 16) u = dpp_umax<0x140>(u);   // row_mirror: halves of the 16-lane row
+  return __uint_as_float(u);
 }
 
-// Code of one element, bit-exact with rint(fl32(x / scale)).
+// scale = fl32(amax / QMAX) for QMAX in {7, 127} without the full division sequence:
+// q0 = amax * c, r = fma(-QMAX, q0, amax), scale = fma(r, c, q0) with c = fl32(1 / QMAX).
+// amax is always a bf16 value (the abs-max of bf16 inputs); the identity with IEEE division was
+// checked exhaustively over all 32640 finite non-negative bf16 values, subnormals included.
 template <int QMAX>
-__device__ __forceinline__ int exact_code(float x, float scale, float inv, bool unsafe) {
-  // |y0 - fl32(x/scale)| <= |x/scale| * (2^-22 + 2^-24 + 2^-24) < (QMAX + 1) * 2^-21
-  constexpr float kTieMargin = static_cast<float>(QMAX + 1) * 0x1p-20f;
-  const float y0 = x * inv;
-  float q0 = rintf(y0);
-  const float d = y0 - q0;  // exact
-  const bool risky = unsafe || fabsf(d) > 0.5f - kTieMargin;
-  if (__builtin_amdgcn_ballot_w64(risky)) {
-    if (risky) {
-      const float h = q0 + copysignf(0.5f, d);      // nearest half-integer, exact
-      const float e = fmaf(-h, scale, x);           // zero exactly when x / scale == h
-      const bool divide = unsafe || e != 0.0f;
-      if (!divide) q0 = rintf(h);
-      if (__builtin_amdgcn_ballot_w64(divide)) {
-        if (divide) q0 = rintf(x / scale);
-      }
-    }
-  }
-  return static_cast<int>(q0);
+__device__ __forceinline__ float scale_of_bf16_amax(float amax) {
+  constexpr float kQ = static_cast<float>(QMAX);
+  constexpr float kC = 1.0f / kQ;
+  const float q0 = amax * kC;
+  const float r = fmaf(-kQ, q0, amax);
+  return fmaf(r, kC, q0);
 }
 
-// Scale of a group from its abs-max, and the helpers exact_code() needs.
+// Group quantizer for QMAX in {7, 127}: scale and the codes (as integral floats) of one lane's
+// 8 elements, bit-exact with rint(fl32(x / scale)).
 template <int QMAX>
-struct GroupScale {
+struct GroupQuantizer {
   float scale, inv;
   bool unsafe;
-  __device__ __forceinline__ explicit GroupScale(float amax) {
-    scale = amax / static_cast<float>(QMAX);  // IEEE division
+  __device__ __forceinline__ explicit GroupQuantizer(float amax) {
+    scale = scale_of_bf16_amax<QMAX>(amax);
     // outside this range rcp or the products may leave the normal range: take the division path
     unsafe = !(scale >= 0x1p-100f && scale <= 0x1p100f) && scale != 0.0f;
     inv = (scale == 0.0f) ? 0.0f : __builtin_amdgcn_rcpf(scale);
   }
-  __device__ __forceinline__ int code(float x) const {
-    const int v = exact_code<QMAX>(x, scale, inv, unsafe);
-    return min(QMAX, max(-QMAX, v));
+  // |y0 - fl32(x/scale)| <= |x/scale| * (2^-22 + 2^-24 + 2^-24) < (QMAX + 1) * 2^-21
+  static constexpr float kTieMargin = static_cast<float>(QMAX + 1) * 0x1p-20f;
+
+  __device__ __forceinline__ float code(float x) const {
+    const float y0 = x * inv;
+    float q = rintf(y0);
+    const float d = y0 - q;  // exact
+    const bool risky = fabsf(d) > 0.5f - kTieMargin;
+    if (__builtin_amdgcn_ballot_w64(risky)) {          // wave-uniform: rarely taken
+      if (risky) {
+        const float h = q + copysignf(0.5f, d);        // nearest half-integer, exact
+        const float e = fmaf(-h, scale, x);            // zero exactly when x / scale == h
+        const bool divide = e != 0.0f;
+        if (!divide) q = rintf(h);
+        if (__builtin_amdgcn_ballot_w64(divide)) {
+          if (divide) q = rintf(x / scale);
+        }
+      }
+    }
+    return q;
+  }
+
+  __device__ __forceinline__ void codes8(const float x[8], float q[8]) const {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) q[i] = code(x[i]);
+    if (__builtin_amdgcn_ballot_w64(unsafe)) {         // extreme magnitudes only
+      if (unsafe) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) q[i] = rintf(x[i] / scale);
+      }
+    }
   }
 };
 
-// int2: codes are -1, 0, +1 and scale = amax.  x / amax is a ratio of two 8-bit significands and
-// cannot round across 1/2, so |code| = 1 exactly when 2|x| > amax (the doubling is exact).
-__device__ __forceinline__ int ternary_code(float x, float amax) {
-  return (2.0f * fabsf(x) > amax) ? (x < 0.0f ? -1 : 1) : 0;
-}
+// int2: codes are -1, 0, +1 and scale = amax.  x / amax is a ratio of two 8-bit significands, so it
+// is either exactly 1/2 (code 0: ties go to even) or at least 1/510 away from it.  Multiplying by a
+// reciprocal shrunk by 2^-20 keeps exact ties below 1/2 and cannot move any other quotient across
+// it, so rint(x * inv) is the exact code.  Extreme magnitudes compare 2|x| > amax instead.
+struct TernaryQuantizer {
+  float amax, inv;
+  bool unsafe;
+  __device__ __forceinline__ explicit TernaryQuantizer(float a) : amax(a) {
+    unsafe = !(a >= 0x1p-100f && a <= 0x1p100f) && a != 0.0f;
+    inv = (a == 0.0f) ? 0.0f : __builtin_amdgcn_rcpf(a) * (1.0f - 0x1p-20f);
+  }
+  __device__ __forceinline__ void codes8(const float x[8], float q[8]) const {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) q[i] = rintf(x[i] * inv);
+    if (__builtin_amdgcn_ballot_w64(unsafe)) {
+      if (unsafe) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) q[i] = (2.0f * fabsf(x[i]) > amax) ? copysignf(1.0f, x[i]) : 0.0f;
+      }
+    }
+  }
+};
 
 __device__ __forceinline__ void unpack_bf16x8(const uint4 raw, float x[8]) {
   const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
@@ -90,6 +130,26 @@ __device__ __forceinline__ float abs_max8(const float x[8]) {
 #pragma unroll
   for (int i = 0; i < 8; ++i) m = fmaxf(m, fabsf(x[i]));
   return m;
+}
+
+// Packing of integral-float codes, done in the float domain: with an offset of 2^(bits-1) every
+// field is non-negative, the weighted sum of up to 16 bits is exact in binary32, and one XOR turns
+// the offset fields into two's complement fields.
+__device__ __forceinline__ uint32_t pack_int4x8(const float q[8]) {
+  const float lo = fmaf(q[3], 4096.0f, fmaf(q[2], 256.0f, fmaf(q[1], 16.0f, q[0]))) + 34952.0f;  // 0x8888
+  const float hi = fmaf(q[7], 4096.0f, fmaf(q[6], 256.0f, fmaf(q[5], 16.0f, q[4]))) + 34952.0f;
+  return (static_cast<uint32_t>(lo) | (static_cast<uint32_t>(hi) << 16)) ^ 0x88888888u;
+}
+__device__ __forceinline__ uint32_t pack_int8x4(const float q[4]) {
+  const float lo = fmaf(q[1], 256.0f, q[0]) + 32896.0f;  // 0x8080
+  const float hi = fmaf(q[3], 256.0f, q[2]) + 32896.0f;
+  return (static_cast<uint32_t>(lo) | (static_cast<uint32_t>(hi) << 16)) ^ 0x80808080u;
+}
+__device__ __forceinline__ uint32_t pack_int2x8(const float q[8]) {
+  float s = q[7];
+#pragma unroll
+  for (int i = 6; i >= 0; --i) s = fmaf(s, 4.0f, q[i]);
+  return static_cast<uint32_t>(s + 43690.0f) ^ 0xAAAAu;  // 0xAAAA
 }
 
 }  // namespace kvp

@@ -49,45 +49,38 @@ template <int BITS>
 __device__ __forceinline__ void store_codes(uint8_t* row_codes, int lane_in_row, const Packed<BITS>& p);
 template <>
 __device__ __forceinline__ void store_codes<8>(uint8_t* row_codes, int lane_in_row, const Packed<8>& p) {
-  *reinterpret_cast<uint2*>(row_codes + lane_in_row * 8) = make_uint2(p.lo, p.hi);
+  store_stream8(row_codes + lane_in_row * 8, make_uint2(p.lo, p.hi));
 }
 template <>
 __device__ __forceinline__ void store_codes<4>(uint8_t* row_codes, int lane_in_row, const Packed<4>& p) {
-  *reinterpret_cast<uint32_t*>(row_codes + lane_in_row * 4) = p.w;
+  store_stream4(row_codes + lane_in_row * 4, p.w);
 }
 template <>
 __device__ __forceinline__ void store_codes<2>(uint8_t* row_codes, int lane_in_row, const Packed<2>& p) {
-  *reinterpret_cast<uint16_t*>(row_codes + lane_in_row * 2) = static_cast<uint16_t>(p.w);
+  store_stream2(row_codes + lane_in_row * 2, p.w);
 }
 
 template <int BITS, int GROUP>
 __device__ __forceinline__ void quantize_lane(const uint4 raw, Packed<BITS>& out, float& scale_out) {
-  constexpr int QMAX = (1 << (BITS - 1)) - 1;
-  float x[8];
+  float x[8], q[8];
   unpack_bf16x8(raw, x);
   const float amax = group_max(abs_max8(x), GROUP / 8);
-
   if constexpr (BITS == 2) {
+    const TernaryQuantizer tq(amax);
     scale_out = amax;  // qmax = 1
-    uint32_t word = 0;
-#pragma unroll
-    for (int i = 0; i < 8; ++i) word |= static_cast<uint32_t>(ternary_code(x[i], amax) & 3) << (2 * i);
-    out.w = word;
+    tq.codes8(x, q);
+    out.w = pack_int2x8(q);
+  } else if constexpr (BITS == 4) {
+    const GroupQuantizer<7> gq(amax);
+    scale_out = gq.scale;
+    gq.codes8(x, q);
+    out.w = pack_int4x8(q);
   } else {
-    const GroupScale<QMAX> gs(amax);
-    scale_out = gs.scale;
-    int q[8];
-#pragma unroll
-    for (int i = 0; i < 8; ++i) q[i] = gs.code(x[i]);
-    if constexpr (BITS == 8) {
-      out.lo = (q[0] & 0xff) | ((q[1] & 0xff) << 8) | ((q[2] & 0xff) << 16) | (static_cast<uint32_t>(q[3]) << 24);
-      out.hi = (q[4] & 0xff) | ((q[5] & 0xff) << 8) | ((q[6] & 0xff) << 16) | (static_cast<uint32_t>(q[7]) << 24);
-    } else {
-      uint32_t word = 0;
-#pragma unroll
-      for (int i = 0; i < 8; ++i) word |= static_cast<uint32_t>(q[i] & 0xf) << (4 * i);
-      out.w = word;
-    }
+    const GroupQuantizer<127> gq(amax);
+    scale_out = gq.scale;
+    gq.codes8(x, q);
+    out.lo = pack_int8x4(q);
+    out.hi = pack_int8x4(q + 4);
   }
 }
 
@@ -96,22 +89,28 @@ __global__ __launch_bounds__(kThreads) void quantize_kernel(const QuantArgs a) {
   constexpr int CB = kHeadDim * BITS / 8;      // code bytes per row
   constexpr int NS = kHeadDim / GROUP;         // scales per row
   constexpr int LANES_PER_GROUP = GROUP / 8;
-  const int lane_in_row = threadIdx.x & (kLanesPerRow - 1);
+  const uint32_t lane_in_row = threadIdx.x & (kLanesPerRow - 1);
   const uint32_t row_in_step = threadIdx.x / kLanesPerRow;
   const uint32_t l = blockIdx.y;
-  const uint32_t row0 = blockIdx.x * kRowsPerBlock + row_in_step;
+  const uint32_t block_row0 = blockIdx.x * kRowsPerBlock;
   const uint32_t valid_rows = a.n_slots * a.H;
+  // block-uniform 64-bit bases, 32-bit per-thread offsets
   const uint16_t* base_l = a.src + static_cast<int64_t>(l) * a.stride_l;
+  const uint16_t* base_blk = base_l + static_cast<int64_t>(block_row0) * a.stride_h;  // linear mode only
+  const int64_t out_row0 = static_cast<int64_t>(l) * a.rows_per_layer + block_row0;
+  uint8_t* codes_blk = a.codes + out_row0 * CB;
+  float* scales_blk = a.scales + out_row0 * NS;
 
   uint4 raw[kSteps];
 #pragma unroll
   for (int s = 0; s < kSteps; ++s) {
-    const uint32_t rr = row0 + s * kRowsPerStep;
+    const uint32_t rloc = row_in_step + s * kRowsPerStep;
+    const uint32_t rr = block_row0 + rloc;
     raw[s] = make_uint4(0, 0, 0, 0);
     if (rr < valid_rows) {
       const uint16_t* row;
       if constexpr (MODE == kLinear) {
-        row = base_l + static_cast<int64_t>(rr) * a.stride_h;
+        row = base_blk + rloc * static_cast<uint32_t>(a.stride_h);
       } else {
         const uint32_t i = a.div_h.quot(rr);
         const uint32_t h = rr - i * a.H;
@@ -130,20 +129,20 @@ __global__ __launch_bounds__(kThreads) void quantize_kernel(const QuantArgs a) {
           row = base_l + ((blk * a.bs + slot) * a.H + h) * kHeadDim;
         }
       }
-      raw[s] = *reinterpret_cast<const uint4*>(row + lane_in_row * 8);
+      raw[s] = load_stream16(row + lane_in_row * 8);
     }
   }
 
 #pragma unroll
   for (int s = 0; s < kSteps; ++s) {
-    const uint32_t rr = row0 + s * kRowsPerStep;
-    if (rr >= a.rows_per_layer) continue;
+    const uint32_t rloc = row_in_step + s * kRowsPerStep;
+    if (block_row0 + rloc >= a.rows_per_layer) continue;
     Packed<BITS> p;
     float scale;
     quantize_lane<BITS, GROUP>(raw[s], p, scale);  // zero rows (padding slots) give zero codes and scales
-    const int64_t out_row = static_cast<int64_t>(l) * a.rows_per_layer + rr;
-    store_codes<BITS>(a.codes + out_row * CB, lane_in_row, p);
-    if ((lane_in_row % LANES_PER_GROUP) == 0) a.scales[out_row * NS + lane_in_row / LANES_PER_GROUP] = scale;
+    store_codes<BITS>(codes_blk + rloc * CB, lane_in_row, p);
+    if ((lane_in_row % LANES_PER_GROUP) == 0)
+      store_stream_f32(scales_blk + rloc * NS + lane_in_row / LANES_PER_GROUP, scale);
   }
 }
 
@@ -183,7 +182,7 @@ extern "C" int32_t kvp_quantize(const kvp_view* src, const kvp_paged* src_paged,
     L = src->L; T = src->T; H = src->H;
     a.src = static_cast<const uint16_t*>(src->ptr);
     a.stride_l = src->stride_l; a.stride_t = src->stride_t; a.stride_h = src->stride_h;
-    mode = (!keep_idx && src->stride_t == H * src->stride_h) ? kLinear : kStrided;
+    mode = (!keep_idx && src->stride_t == H * src->stride_h && src->stride_h < (1 << 20)) ? kLinear : kStrided;
   } else {
     rc = check_paged(src_paged);
     if (rc != KVP_OK) return rc;

@@ -47,12 +47,12 @@ def library_path() -> str:
     return _LIB_PATH
 
 
-def _load():
-    if not os.path.exists(_LIB_PATH):
+def _load(path: str = _LIB_PATH):
+    if not os.path.exists(path):
         raise ImportError(
-            f"{_LIB_PATH} is not built; run `python -m paper_2512_14946_amd.build` "
+            f"{path} is not built; run `python -m paper_2512_14946_amd.build` "
             "(there is no CPU fallback for the kvp_* operations)")
-    lib = ctypes.CDLL(_LIB_PATH)
+    lib = ctypes.CDLL(path)
     P = ctypes.POINTER
     lib.kvp_quantize.restype = _i32
     lib.kvp_quantize.argtypes = [P(_View), P(_Paged), _vp, _i64, P(_QPlane), _vp]

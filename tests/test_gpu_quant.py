@@ -142,3 +142,26 @@ def test_quantize_argument_errors_enqueue_nothing():
         kvp.kvp_quantize(x.view(-1)[4:4 + 8 * 8 * 128].view(1, 8, 8, 128), kvp.alloc_qplane(1, 8, 8, 128, 4, 64, DEV))
     assert e.value.code == -2
     torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("bits", [8, 4])
+def test_scale_exact_for_every_bf16_amax(bits):
+    # the kernel derives the scale from the group abs-max with a short fma sequence instead of a
+    # division: check it against the oracle's IEEE division for every finite bf16 magnitude
+    kvp = _kvp()
+    _say("all bf16 amax", bits)
+    mags = np.arange(0, 0x7F80, dtype=np.uint16)                    # every finite non-negative bf16
+    n = len(mags)
+    T = (n + 7) // 8
+    xb = np.zeros((1, T, 8, 128), dtype=np.uint16)
+    flat = xb.reshape(-1, 128)
+    flat[:n, 3] = mags                                             # group 0 of each row
+    flat[:n, 40] = mags | 0x8000                                   # group 1: the same magnitude, negative
+    flat[:n, 41] = (mags >> 1)                                     # plus some smaller element
+    x = bits_to_torch(xb, DEV)
+    qp = kvp.alloc_qplane(1, T, 8, 128, bits, 32, DEV)
+    kvp.kvp_quantize(x, qp)
+    torch.cuda.synchronize()
+    oc, os_ = oracle.quantize(xb, bits, 32, Tp=qp.Tp)
+    assert np.array_equal(qp.scales.cpu().numpy().view(np.uint32), os_.view(np.uint32))
+    assert np.array_equal(qp.codes.cpu().numpy(), oc)
