@@ -7,13 +7,18 @@
 //
 // Pipeline (all on the caller's stream, scratch in the caller's workspace):
 //   1. token scores of the unquantized K (kvp_score_tokens, causal, window forced);
-//   2. one top-k keep list per distinct keep_k < T (kvp_select_topk's kernel);
-//   3. reference pass: O_full and sum O_full^2 per (layer, kv head, 128-row block);
-//   4. one "stream" per distinct (bits, group, keep_k): attention of the window rows over the kept
-//      tokens with K and V quantized and dequantized on the fly, compared with O_full;
-//   5. a single-block reduction in a fixed order (deterministic) to loss[] and partial[].
+//   2. one top-k keep list per distinct keep_k < T (kvp_select_topk's kernel); the keep-sets are
+//      nested (the ranking is a total order), so the tokens split into shells: shell j holds the
+//      tokens that enter the keep-set at the j-th smallest keep_k.  One kernel turns the lists into
+//      a permutation of the tokens ordered by shell;
+//   3. reference pass over all tokens in that order: O_full and sum O_full^2;
+//   4. ONE stream per distinct (bits, group): attention of the window rows over the tokens in shell
+//      order with K and V quantized and dequantized on the fly; at every shell boundary the running
+//      output is the output of that keep level and is compared with O_full.  Every candidate keep
+//      level of a codec therefore costs one pass over its largest keep-set instead of one pass each;
+//   5. a reduction in a fixed order (deterministic) to loss[] and partial[].
 //
-// The attention kernel (steps 3 and 4) walks the kept tokens in tiles of 32.  Per tile: 256 threads
+// The attention kernel (steps 3 and 4) walks the tokens in tiles of 32.  Per tile: 256 threads
 // load 32 K rows and 32 V rows (16 lanes per row, 8 channels per lane), run the bit-exact group
 // quantizer and dequantizer of quant_device.h on them, and stage K-hat as bf16 and V-hat as fp32
 // in LDS.  Each of the 4 waves owns 32 of the block's 128 query rows (stationary MFMA operand in
@@ -42,7 +47,6 @@ constexpr float kLog2e = 1.4426950408889634f;
 
 struct StreamDesc {
   int32_t bits, group;   // bits == 16: no quantization
-  int32_t level;         // index into EvalArgs::level_k / level_idx
 };
 
 struct EvalArgs {
@@ -55,13 +59,16 @@ struct EvalArgs {
   int32_t T, W, G, Hkv, M, RB, L;
   float scale2;
   int32_t n_streams, n_cfgs, n_levels;
-  int32_t level_k[kMaxLevels];
-  const int32_t* level_idx[kMaxLevels];  // [L*Hkv][k] ascending keep list, or null = all tokens in order
+  int32_t level_k[kMaxLevels];           // ascending
+  const int32_t* level_idx[kMaxLevels];  // [L*Hkv][k] ascending keep list, or null when k == T
   StreamDesc streams[kMaxCfgs];
-  uint8_t cfg_stream[kMaxCfgs];
+  uint8_t cfg_stream[kMaxCfgs], cfg_level[kMaxCfgs];
+  uint8_t* shell;   // [L*Hkv][T] scratch: index of the first keep level that holds the token
+  int32_t* order;   // [L*Hkv][T] tokens ordered by shell, ascending inside a shell
   float* o_full;    // [L*Hkv][RB][128][128]
   float* den_part;  // [L*Hkv][RB]
-  float* num_part;  // [L*Hkv][RB][n_streams]
+  float* num_part;  // [L*Hkv][RB][n_streams][n_levels]
+  double* layer_part;  // [L][n_cfgs][2] scratch of the final reduction
   float* loss;      // [n_cfgs]
   float* partial;   // [L][n_cfgs][2] or null
 };
@@ -114,6 +121,63 @@ __device__ __forceinline__ float block_sum(float v, float* red) {
   return red[0] + red[1] + red[2] + red[3];
 }
 
+// Tokens of one (layer, kv head) ordered by shell.  One 1024-thread block per row: the keep lists
+// are scattered into a shell id per token (largest level first, so the smallest level wins), then a
+// counting sort by (shell, token) writes the permutation.
+constexpr int kOrderThreads = 1024;
+__global__ __launch_bounds__(kOrderThreads) void build_order_kernel(const EvalArgs a) {
+  __shared__ uint32_t count_s[kMaxLevels + 1][kOrderThreads];
+  __shared__ uint32_t wave_s[kOrderThreads / 64];
+  __shared__ uint32_t carry_s;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int64_t lh = blockIdx.x;
+  uint8_t* shell = a.shell + lh * a.T;
+  int32_t* order = a.order + lh * a.T;
+  const int n_shells = a.n_levels + 1;  // the last shell holds the tokens no keep level contains
+
+  for (int t = tid; t < a.T; t += kOrderThreads) shell[t] = static_cast<uint8_t>(a.n_levels);
+  __syncthreads();
+  for (int j = a.n_levels - 1; j >= 0; --j) {
+    const int32_t* list = a.level_idx[j];
+    if (list) {
+      list += lh * a.level_k[j];
+      for (int i = tid; i < a.level_k[j]; i += kOrderThreads) shell[min(max(list[i], 0), a.T - 1)] = static_cast<uint8_t>(j);
+    } else {
+      for (int t = tid; t < a.T; t += kOrderThreads) shell[t] = static_cast<uint8_t>(j);
+    }
+    __syncthreads();
+  }
+  // thread tid owns the contiguous token range [t0, t1)
+  const int per = (a.T + kOrderThreads - 1) / kOrderThreads;
+  const int t0 = min(a.T, tid * per), t1 = min(a.T, t0 + per);
+  for (int sidx = 0; sidx < n_shells; ++sidx) count_s[sidx][tid] = 0;
+  for (int t = t0; t < t1; ++t) count_s[shell[t]][tid] += 1;
+  if (tid == 0) carry_s = 0;
+  __syncthreads();
+  // exclusive scan over (shell major, thread minor); count_s becomes the first output slot
+  for (int sidx = 0; sidx < n_shells; ++sidx) {
+    const uint32_t mine = count_s[sidx][tid];
+    uint32_t incl = mine;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+      const uint32_t n = __shfl_up(incl, off, 64);
+      if (lane >= off) incl += n;
+    }
+    if (lane == 63) wave_s[wave] = incl;
+    __syncthreads();
+    uint32_t before = carry_s;
+    for (int w = 0; w < wave; ++w) before += wave_s[w];
+    count_s[sidx][tid] = before + incl - mine;
+    __syncthreads();
+    if (tid == kOrderThreads - 1) carry_s = before + incl;
+    __syncthreads();
+  }
+  for (int t = t0; t < t1; ++t) {
+    const uint32_t pos = count_s[shell[t]][tid]++;
+    order[pos] = t;
+  }
+}
+
 // REFERENCE: stream = (16 bits, all tokens); writes O_full and the denominator.
 template <bool REFERENCE>
 __global__ __launch_bounds__(kThreads) void attention_kernel(const EvalArgs a) {
@@ -128,16 +192,12 @@ __global__ __launch_bounds__(kThreads) void attention_kernel(const EvalArgs a) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int rb = blockIdx.x, lh = blockIdx.y;
   const int l = lh / a.Hkv, h = lh - l * a.Hkv;
-  int bits = 16, group = 128, n_tok = a.T;
-  const int32_t* list = nullptr;
+  int bits = 16, group = 128;
   if constexpr (!REFERENCE) {
-    const StreamDesc sd = a.streams[blockIdx.z];
-    bits = sd.bits;
-    group = sd.group;
-    n_tok = a.level_k[sd.level];
-    list = a.level_idx[sd.level];
-    if (list) list += static_cast<int64_t>(lh) * n_tok;
+    bits = a.streams[blockIdx.z].bits;
+    group = a.streams[blockIdx.z].group;
   }
+  const int32_t* order = a.order + static_cast<int64_t>(lh) * a.T;
   const uint16_t* kbase = a.k + static_cast<int64_t>(l) * a.k_sl + static_cast<int64_t>(h) * a.k_sh;
   const uint16_t* vbase = a.v + static_cast<int64_t>(l) * a.v_sl + static_cast<int64_t>(h) * a.v_sh;
   const int win0 = a.T - a.W;
@@ -168,168 +228,188 @@ __global__ __launch_bounds__(kThreads) void attention_kernel(const EvalArgs a) {
   for (int i = 0; i < 8; ++i)
 #pragma unroll
     for (int j = 0; j < 8; ++j) o[i][j] = 0.0f;
+  float* ofull = a.o_full + (static_cast<int64_t>(lh) * a.RB + rb) * kRowsPerBlock * kHeadDim;
 
-  for (int pos0 = 0; pos0 < n_tok; pos0 += kTile) {
-    __syncthreads();  // the previous tile's LDS is no longer read
-    // ---- stage 32 tokens: K-hat (bf16) and V-hat (fp32) ----
-    bool has_window = false;
+  // segments end at the keep levels (tiles never straddle a level boundary, so the state at a
+  // boundary is exactly that level's attention).  The reference walks the same tiles, plus the
+  // tokens no level keeps, and only looks at its state at the very end: a 16-bit stream is then
+  // bit-identical to it wherever the two cover the same tokens.
+  const int n_seg = a.n_levels + ((REFERENCE && a.level_k[a.n_levels - 1] < a.T) ? 1 : 0);
+  int pos0 = 0;
+  for (int seg = 0; seg < n_seg; ++seg) {
+    const int seg_end = seg < a.n_levels ? a.level_k[seg] : a.T;
+    for (; pos0 < seg_end; pos0 += kTile) {
+      __syncthreads();  // the previous tile's LDS is no longer read
+      // ---- stage 32 tokens: K-hat (bf16) and V-hat (fp32) ----
+      bool has_window = false;
 #pragma unroll
-    for (int s = 0; s < 2; ++s) {
-      const int slot = tid + s * kThreads;
-      const int tk = slot >> 4, part = slot & 15;
-      const int pos = pos0 + tk;
-      uint4 kraw = make_uint4(0, 0, 0, 0), vraw = make_uint4(0, 0, 0, 0);
-      int t = 0x7fffffff;  // beyond every query position: masked
-      if (pos < n_tok) {
-        t = list ? list[pos] : pos;
-        t = min(max(t, 0), a.T - 1);
-        kraw = *reinterpret_cast<const uint4*>(kbase + static_cast<int64_t>(t) * a.k_st + part * 8);
-        vraw = *reinterpret_cast<const uint4*>(vbase + static_cast<int64_t>(t) * a.v_st + part * 8);
+      for (int s = 0; s < 2; ++s) {
+        const int slot = tid + s * kThreads;
+        const int tk = slot >> 4, part = slot & 15;
+        const int pos = pos0 + tk;
+        uint4 kraw = make_uint4(0, 0, 0, 0), vraw = make_uint4(0, 0, 0, 0);
+        int t = 0x7fffffff;  // beyond every query position: masked
+        if (pos < seg_end) {
+          t = min(max(order[pos], 0), a.T - 1);
+          kraw = *reinterpret_cast<const uint4*>(kbase + static_cast<int64_t>(t) * a.k_st + part * 8);
+          vraw = *reinterpret_cast<const uint4*>(vbase + static_cast<int64_t>(t) * a.v_st + part * 8);
+        }
+        float ky[8], vy[8];
+        fake_quant8(kraw, bits, group, ky);
+        fake_quant8(vraw, bits, group, vy);
+        uint4 kp;
+        kp.x = (__float_as_uint(ky[0]) >> 16) | (__float_as_uint(ky[1]) & 0xffff0000u);
+        kp.y = (__float_as_uint(ky[2]) >> 16) | (__float_as_uint(ky[3]) & 0xffff0000u);
+        kp.z = (__float_as_uint(ky[4]) >> 16) | (__float_as_uint(ky[5]) & 0xffff0000u);
+        kp.w = (__float_as_uint(ky[6]) >> 16) | (__float_as_uint(ky[7]) & 0xffff0000u);
+        *reinterpret_cast<uint4*>(k_s + tk * kPitch + part * 8) = kp;
+        *reinterpret_cast<float4*>(v_s + tk * kHeadDim + part * 8) = make_float4(vy[0], vy[1], vy[2], vy[3]);
+        *reinterpret_cast<float4*>(v_s + tk * kHeadDim + part * 8 + 4) = make_float4(vy[4], vy[5], vy[6], vy[7]);
+        if (part == 0) tok_s[tk] = t;
+        has_window |= (t >= win0);
       }
-      float ky[8], vy[8];
-      fake_quant8(kraw, bits, group, ky);
-      fake_quant8(vraw, bits, group, vy);
-      uint4 kp;
-      kp.x = (__float_as_uint(ky[0]) >> 16) | (__float_as_uint(ky[1]) & 0xffff0000u);
-      kp.y = (__float_as_uint(ky[2]) >> 16) | (__float_as_uint(ky[3]) & 0xffff0000u);
-      kp.z = (__float_as_uint(ky[4]) >> 16) | (__float_as_uint(ky[5]) & 0xffff0000u);
-      kp.w = (__float_as_uint(ky[6]) >> 16) | (__float_as_uint(ky[7]) & 0xffff0000u);
-      *reinterpret_cast<uint4*>(k_s + tk * kPitch + part * 8) = kp;
-      *reinterpret_cast<float4*>(v_s + tk * kHeadDim + part * 8) = make_float4(vy[0], vy[1], vy[2], vy[3]);
-      *reinterpret_cast<float4*>(v_s + tk * kHeadDim + part * 8 + 4) = make_float4(vy[4], vy[5], vy[6], vy[7]);
-      if (part == 0) tok_s[tk] = t;
-      has_window |= (t >= win0);
-    }
-    const bool need_mask = __syncthreads_or(has_window ? 1 : 0) != 0;  // also publishes the stage
+      const bool need_mask = __syncthreads_or(has_window ? 1 : 0) != 0;  // also publishes the stage
 
-    // ---- logits of 32 keys x this wave's 32 queries, online softmax ----
-    {
-      floatx16 acc = {0};
-      const uint16_t* krow = k_s + (lane & 31) * kPitch + (lane >> 5) * 8;
+      // ---- logits of 32 keys x this wave's 32 queries, online softmax ----
+      {
+        floatx16 acc = {0};
+        const uint16_t* krow = k_s + (lane & 31) * kPitch + (lane >> 5) * 8;
 #pragma unroll
-      for (int ks = 0; ks < 8; ++ks)
-        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(*reinterpret_cast<const uint4*>(krow + ks * 16)), q[ks],
-                                                      acc, 0, 0, 0);
-      float s[16];
-      float tmax = -INFINITY;
+        for (int ks = 0; ks < 8; ++ks)
+          acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(*reinterpret_cast<const uint4*>(krow + ks * 16)),
+                                                        q[ks], acc, 0, 0, 0);
+        if (need_mask) {
 #pragma unroll
-      for (int vv = 0; vv < 16; ++vv) {
-        s[vv] = acc[vv] * a.scale2;
-        if (need_mask && tok_s[acc_row(lane, vv)] > qpos) s[vv] = -INFINITY;
-        tmax = fmaxf(tmax, s[vv]);
+          for (int vv = 0; vv < 16; ++vv)
+            if (tok_s[acc_row(lane, vv)] > qpos) acc[vv] = -INFINITY;
+        }
+        float tmax = acc[0];
+#pragma unroll
+        for (int vv = 1; vv < 16; ++vv) tmax = fmaxf(tmax, acc[vv]);
+        tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
+        const float m_new = fmaxf(run_m, tmax * a.scale2);  // scale2 > 0: max commutes with it
+        const float m_safe = (m_new == -INFINITY) ? 0.0f : m_new;
+        const float alpha = __builtin_amdgcn_exp2f(run_m - m_safe);
+        float zsum = 0.0f;
+        const int rloc = wave * 32 + (lane & 31);
+#pragma unroll
+        for (int vv = 0; vv < 16; ++vv) {
+          const float p = __builtin_amdgcn_exp2f(fmaf(acc[vv], a.scale2, -m_safe));
+          zsum += p;
+          p_s[acc_row(lane, vv) * kRowsPerBlock + rloc] = p;
+        }
+        run_z = run_z * alpha + zsum;
+        run_m = m_new;
+        if (lane < 32) alpha_s[rloc] = alpha;
       }
-      tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
-      const float m_new = fmaxf(run_m, tmax);
-      const float m_safe = (m_new == -INFINITY) ? 0.0f : m_new;
-      const float alpha = __builtin_amdgcn_exp2f(run_m - m_safe);
-      float zsum = 0.0f;
-      const int rloc = wave * 32 + (lane & 31);
-#pragma unroll
-      for (int vv = 0; vv < 16; ++vv) {
-        const float p = __builtin_amdgcn_exp2f(s[vv] - m_safe);
-        zsum += p;
-        p_s[acc_row(lane, vv) * kRowsPerBlock + rloc] = p;
-      }
-      run_z = run_z * alpha + zsum;
-      run_m = m_new;
-      if (lane < 32) alpha_s[rloc] = alpha;
-    }
-    __syncthreads();
+      __syncthreads();
 
-    // ---- O = O * alpha + P V on the vector ALU ----
-    {
-      const float4 a0 = *reinterpret_cast<const float4*>(alpha_s + 4 * ty);
-      const float4 a1 = *reinterpret_cast<const float4*>(alpha_s + 64 + 4 * ty);
-      const float al[8] = {a0.x, a0.y, a0.z, a0.w, a1.x, a1.y, a1.z, a1.w};
-#pragma unroll
-      for (int i = 0; i < 8; ++i)
-#pragma unroll
-        for (int j = 0; j < 8; ++j) o[i][j] *= al[i];
-#pragma unroll 4
-      for (int tk = 0; tk < kTile; ++tk) {
-        const float4 p0 = *reinterpret_cast<const float4*>(p_s + tk * kRowsPerBlock + 4 * ty);
-        const float4 p1 = *reinterpret_cast<const float4*>(p_s + tk * kRowsPerBlock + 64 + 4 * ty);
-        const float4 v0 = *reinterpret_cast<const float4*>(v_s + tk * kHeadDim + 4 * tx);
-        const float4 v1 = *reinterpret_cast<const float4*>(v_s + tk * kHeadDim + 64 + 4 * tx);
-        const float pr[8] = {p0.x, p0.y, p0.z, p0.w, p1.x, p1.y, p1.z, p1.w};
-        const float vc[8] = {v0.x, v0.y, v0.z, v0.w, v1.x, v1.y, v1.z, v1.w};
+      // ---- O = O * alpha + P V on the vector ALU ----
+      {
+        const float4 a0 = *reinterpret_cast<const float4*>(alpha_s + 4 * ty);
+        const float4 a1 = *reinterpret_cast<const float4*>(alpha_s + 64 + 4 * ty);
+        const float al[8] = {a0.x, a0.y, a0.z, a0.w, a1.x, a1.y, a1.z, a1.w};
 #pragma unroll
         for (int i = 0; i < 8; ++i)
 #pragma unroll
-          for (int j = 0; j < 8; ++j) o[i][j] = fmaf(pr[i], vc[j], o[i][j]);
+          for (int j = 0; j < 8; ++j) o[i][j] *= al[i];
+#pragma unroll 4
+        for (int tk = 0; tk < kTile; ++tk) {
+          const float4 p0 = *reinterpret_cast<const float4*>(p_s + tk * kRowsPerBlock + 4 * ty);
+          const float4 p1 = *reinterpret_cast<const float4*>(p_s + tk * kRowsPerBlock + 64 + 4 * ty);
+          const float4 v0 = *reinterpret_cast<const float4*>(v_s + tk * kHeadDim + 4 * tx);
+          const float4 v1 = *reinterpret_cast<const float4*>(v_s + tk * kHeadDim + 64 + 4 * tx);
+          const float pr[8] = {p0.x, p0.y, p0.z, p0.w, p1.x, p1.y, p1.z, p1.w};
+          const float vc[8] = {v0.x, v0.y, v0.z, v0.w, v1.x, v1.y, v1.z, v1.w};
+#pragma unroll
+          for (int i = 0; i < 8; ++i)
+#pragma unroll
+            for (int j = 0; j < 8; ++j) o[i][j] = fmaf(pr[i], vc[j], o[i][j]);
+        }
       }
     }
-  }
+    pos0 = seg_end;
+    if (REFERENCE && seg != n_seg - 1) continue;
 
-  // ---- normalize, then store (reference) or compare with the reference ----
-  {
-    const float z = run_z + __shfl_xor(run_z, 32, 64);
-    __syncthreads();
-    if (lane < 32) z_s[wave * 32 + lane] = z;
-    __syncthreads();
-  }
-  float sq = 0.0f;
-  float* ofull = a.o_full + (static_cast<int64_t>(lh) * a.RB + rb) * kRowsPerBlock * kHeadDim;
+    // ---- end of a segment: normalize a copy, then store (reference) or compare with the reference ----
+    {
+      const float z = run_z + __shfl_xor(run_z, 32, 64);
+      __syncthreads();
+      if (lane < 32) z_s[wave * 32 + lane] = z;
+      __syncthreads();
+    }
+    float sq = 0.0f;
 #pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    const int rloc = (i < 4) ? 4 * ty + i : 64 + 4 * ty + (i - 4);
-    const bool live = rb * kRowsPerBlock + rloc < a.M;
-    const float inv = 1.0f / z_s[rloc];
+    for (int i = 0; i < 8; ++i) {
+      const int rloc = (i < 4) ? 4 * ty + i : 64 + 4 * ty + (i - 4);
+      const bool live = rb * kRowsPerBlock + rloc < a.M;
+      const float inv = 1.0f / z_s[rloc];
 #pragma unroll
-    for (int jh = 0; jh < 2; ++jh) {
-      const int c0 = jh * 64 + 4 * tx;
-      float4 val = make_float4(o[i][jh * 4 + 0] * inv, o[i][jh * 4 + 1] * inv, o[i][jh * 4 + 2] * inv,
-                               o[i][jh * 4 + 3] * inv);
-      float4* dst = reinterpret_cast<float4*>(ofull + rloc * kHeadDim + c0);
-      if constexpr (REFERENCE) {
-        *dst = val;
-        if (live) sq += val.x * val.x + val.y * val.y + val.z * val.z + val.w * val.w;
-      } else {
-        const float4 ref = *dst;
-        const float dx = val.x - ref.x, dy = val.y - ref.y, dz = val.z - ref.z, dw = val.w - ref.w;
-        if (live) sq += dx * dx + dy * dy + dz * dz + dw * dw;
+      for (int jh = 0; jh < 2; ++jh) {
+        const int c0 = jh * 64 + 4 * tx;
+        const float4 val = make_float4(o[i][jh * 4 + 0] * inv, o[i][jh * 4 + 1] * inv, o[i][jh * 4 + 2] * inv,
+                                       o[i][jh * 4 + 3] * inv);
+        float4* dst = reinterpret_cast<float4*>(ofull + rloc * kHeadDim + c0);
+        if constexpr (REFERENCE) {
+          *dst = val;
+          if (live) sq += val.x * val.x + val.y * val.y + val.z * val.z + val.w * val.w;
+        } else {
+          const float4 ref = *dst;
+          const float dx = val.x - ref.x, dy = val.y - ref.y, dz = val.z - ref.z, dw = val.w - ref.w;
+          if (live) sq += dx * dx + dy * dy + dz * dz + dw * dw;
+        }
       }
     }
-  }
-  const float total = block_sum(sq, red_s);
-  if (tid == 0) {
-    if constexpr (REFERENCE) {
-      a.den_part[static_cast<int64_t>(lh) * a.RB + rb] = total;
-    } else {
-      a.num_part[(static_cast<int64_t>(lh) * a.RB + rb) * a.n_streams + blockIdx.z] = total;
+    const float total = block_sum(sq, red_s);
+    if (tid == 0) {
+      if constexpr (REFERENCE) {
+        a.den_part[static_cast<int64_t>(lh) * a.RB + rb] = total;
+      } else {
+        a.num_part[((static_cast<int64_t>(lh) * a.RB + rb) * a.n_streams + blockIdx.z) * a.n_levels + seg] = total;
+      }
     }
   }
 }
 
-// Fixed-order reduction: thread c owns configuration c.
-__global__ void finish_kernel(const EvalArgs a) {
-  const int c = threadIdx.x;
-  if (c >= a.n_cfgs) return;
-  const int s = a.cfg_stream[c];
-  double num = 0.0, den = 0.0;
-  for (int l = 0; l < a.L; ++l) {
+// Fixed-order reduction.  Thread (c, l) sums one layer of one configuration over kv heads and row
+// blocks; then thread c adds the layers in order.
+constexpr int kFinishThreads = 1024;
+__global__ __launch_bounds__(kFinishThreads) void finish_kernel(const EvalArgs a) {
+  double* layer_s = a.layer_part;  // [L][n_cfgs][2]
+  for (int item = threadIdx.x; item < a.n_cfgs * a.L; item += kFinishThreads) {
+    const int c = item % a.n_cfgs, l = item / a.n_cfgs;
+    const int s = a.cfg_stream[c], lev = a.cfg_level[c];
     double num_l = 0.0, den_l = 0.0;
     for (int h = 0; h < a.Hkv; ++h)
       for (int rb = 0; rb < a.RB; ++rb) {
         const int64_t cell = (static_cast<int64_t>(l) * a.Hkv + h) * a.RB + rb;
-        num_l += static_cast<double>(a.num_part[cell * a.n_streams + s]);
+        num_l += static_cast<double>(a.num_part[(cell * a.n_streams + s) * a.n_levels + lev]);
         den_l += static_cast<double>(a.den_part[cell]);
       }
+    layer_s[(l * a.n_cfgs + c) * 2 + 0] = num_l;
+    layer_s[(l * a.n_cfgs + c) * 2 + 1] = den_l;
     if (a.partial) {
       a.partial[(static_cast<int64_t>(l) * a.n_cfgs + c) * 2 + 0] = static_cast<float>(num_l);
       a.partial[(static_cast<int64_t>(l) * a.n_cfgs + c) * 2 + 1] = static_cast<float>(den_l);
     }
-    num += num_l;
-    den += den_l;
   }
-  a.loss[c] = static_cast<float>(sqrt(num / den));
+  __syncthreads();
+  if (threadIdx.x < a.n_cfgs) {
+    const int c = threadIdx.x;
+    double num = 0.0, den = 0.0;
+    for (int l = 0; l < a.L; ++l) {
+      num += layer_s[(l * a.n_cfgs + c) * 2 + 0];
+      den += layer_s[(l * a.n_cfgs + c) * 2 + 1];
+    }
+    a.loss[c] = static_cast<float>(sqrt(num / den));
+  }
 }
 
 size_t align256(size_t n) { return (n + 255) / 256 * 256; }
 
 struct EvalPlan {
   int64_t LH, M, RB;
-  size_t score_ws, scores, idx, o_full, den, num, total;
+  size_t score_ws, scores, idx, shell, order, o_full, den, num, layer, total;
 };
 
 EvalPlan make_plan(int64_t L, int64_t Hkv, int64_t Hq, int64_t W, int64_t T, int32_t n_cfgs) {
@@ -337,14 +417,18 @@ EvalPlan make_plan(int64_t L, int64_t Hkv, int64_t Hq, int64_t W, int64_t T, int
   p.LH = L * Hkv;
   p.M = (Hq / Hkv) * W;
   p.RB = ceil_div(p.M, kRowsPerBlock);
-  const int64_t levels = n_cfgs < kMaxLevels ? (n_cfgs > 0 ? n_cfgs : 1) : kMaxLevels;
+  const int64_t cfgs = n_cfgs > 0 ? n_cfgs : 1;
+  const int64_t levels = cfgs < kMaxLevels ? cfgs : kMaxLevels;
   p.score_ws = align256(kvp_score_workspace_bytes(L, Hkv, Hq, W, T));
   p.scores = align256(static_cast<size_t>(p.LH) * T * sizeof(float));
   p.idx = align256(static_cast<size_t>(levels) * p.LH * T * sizeof(int32_t));
+  p.shell = align256(static_cast<size_t>(p.LH) * T);
+  p.order = align256(static_cast<size_t>(p.LH) * T * sizeof(int32_t));
   p.o_full = align256(static_cast<size_t>(p.LH) * p.RB * kRowsPerBlock * kHeadDim * sizeof(float));
   p.den = align256(static_cast<size_t>(p.LH) * p.RB * sizeof(float));
-  p.num = align256(static_cast<size_t>(p.LH) * p.RB * (n_cfgs > 0 ? n_cfgs : 1) * sizeof(float));
-  p.total = p.score_ws + p.scores + p.idx + p.o_full + p.den + p.num;
+  p.num = align256(static_cast<size_t>(p.LH) * p.RB * cfgs * levels * sizeof(float));
+  p.layer = align256(static_cast<size_t>(L) * cfgs * 2 * sizeof(double));
+  p.total = p.score_ws + p.scores + p.idx + p.shell + p.order + p.o_full + p.den + p.num + p.layer;
   return p;
 }
 
@@ -375,40 +459,49 @@ extern "C" int32_t kvp_eval_configs(const kvp_view* q_win, const kvp_view* k, co
   if (L * Hkv > 65535 || T >= (1ll << 30)) return KVP_ERR_SHAPE;
 
   EvalArgs a{};
-  // distinct keep levels and distinct (bits, group, level) streams
+  // distinct keep levels (ascending) and distinct (bits, group) streams
   for (int32_t c = 0; c < n_cfgs; ++c) {
     const kvp_config& cf = cfgs[c];
     if (cf.bits != 16 && cf.bits != 8 && cf.bits != 4 && cf.bits != 2) return KVP_ERR_UNSUPPORTED;
     if (cf.bits != 16 && cf.group != 32 && cf.group != 64 && cf.group != 128) return KVP_ERR_UNSUPPORTED;
     if (cf.keep_k < 1 || cf.keep_k > T) return KVP_ERR_SHAPE;
-    int lev = -1;
-    for (int j = 0; j < a.n_levels; ++j)
-      if (a.level_k[j] == cf.keep_k) lev = j;
-    if (lev < 0) {
+    bool known = false;
+    for (int j = 0; j < a.n_levels; ++j) known |= a.level_k[j] == cf.keep_k;
+    if (!known) {
       if (a.n_levels == kMaxLevels) return KVP_ERR_UNSUPPORTED;
-      lev = a.n_levels++;
-      a.level_k[lev] = static_cast<int32_t>(cf.keep_k);
+      int j = a.n_levels++;
+      for (; j > 0 && a.level_k[j - 1] > cf.keep_k; --j) a.level_k[j] = a.level_k[j - 1];  // insertion sort
+      a.level_k[j] = static_cast<int32_t>(cf.keep_k);
     }
+  }
+  for (int32_t c = 0; c < n_cfgs; ++c) {
+    const kvp_config& cf = cfgs[c];
+    for (int j = 0; j < a.n_levels; ++j)
+      if (a.level_k[j] == cf.keep_k) a.cfg_level[c] = static_cast<uint8_t>(j);
     const int32_t grp = cf.bits == 16 ? 128 : cf.group;
     int s = -1;
     for (int j = 0; j < a.n_streams; ++j)
-      if (a.streams[j].bits == cf.bits && a.streams[j].group == grp && a.streams[j].level == lev) s = j;
+      if (a.streams[j].bits == cf.bits && a.streams[j].group == grp) s = j;
     if (s < 0) {
       s = a.n_streams++;
-      a.streams[s] = StreamDesc{cf.bits, grp, lev};
+      a.streams[s] = StreamDesc{cf.bits, grp};
     }
     a.cfg_stream[c] = static_cast<uint8_t>(s);
   }
 
   const EvalPlan p = make_plan(L, Hkv, Hq, W, T, n_cfgs);
   if (!ws || ws_bytes < p.total || (reinterpret_cast<uintptr_t>(ws) & 15u)) return KVP_ERR_WORKSPACE;
-  char* base = static_cast<char*>(ws);
-  void* score_ws = base;
-  float* scores = reinterpret_cast<float*>(base + p.score_ws);
-  int32_t* idx = reinterpret_cast<int32_t*>(base + p.score_ws + p.scores);
-  a.o_full = reinterpret_cast<float*>(base + p.score_ws + p.scores + p.idx);
-  a.den_part = reinterpret_cast<float*>(base + p.score_ws + p.scores + p.idx + p.o_full);
-  a.num_part = reinterpret_cast<float*>(base + p.score_ws + p.scores + p.idx + p.o_full + p.den);
+  char* cursor = static_cast<char*>(ws);
+  auto take = [&cursor](size_t bytes) { char* r = cursor; cursor += bytes; return r; };
+  void* score_ws = take(p.score_ws);
+  float* scores = reinterpret_cast<float*>(take(p.scores));
+  int32_t* idx = reinterpret_cast<int32_t*>(take(p.idx));
+  a.shell = reinterpret_cast<uint8_t*>(take(p.shell));
+  a.order = reinterpret_cast<int32_t*>(take(p.order));
+  a.o_full = reinterpret_cast<float*>(take(p.o_full));
+  a.den_part = reinterpret_cast<float*>(take(p.den));
+  a.num_part = reinterpret_cast<float*>(take(p.num));
+  a.layer_part = reinterpret_cast<double*>(take(p.layer));
 
   a.q = static_cast<const uint16_t*>(q_win->ptr);
   a.q_sl = q_win->stride_l; a.q_st = q_win->stride_t; a.q_sh = q_win->stride_h;
@@ -429,16 +522,17 @@ extern "C" int32_t kvp_eval_configs(const kvp_view* q_win, const kvp_view* k, co
   if (rc != KVP_OK) return rc;
   for (int j = 0; j < a.n_levels; ++j) {
     if (a.level_k[j] == T) {
-      a.level_idx[j] = nullptr;  // all tokens, in order
+      a.level_idx[j] = nullptr;  // every token
     } else {
       int32_t* out = idx + static_cast<int64_t>(j) * p.LH * T;
       select_topk_launch(scores, p.LH, T, T, a.level_k[j], out, st);
       a.level_idx[j] = out;
     }
   }
+  build_order_kernel<<<dim3(static_cast<unsigned>(p.LH)), kOrderThreads, 0, st>>>(a);
   attention_kernel<true><<<dim3(static_cast<unsigned>(p.RB), static_cast<unsigned>(p.LH), 1), kThreads, 0, st>>>(a);
   attention_kernel<false><<<dim3(static_cast<unsigned>(p.RB), static_cast<unsigned>(p.LH),
                                  static_cast<unsigned>(a.n_streams)), kThreads, 0, st>>>(a);
-  finish_kernel<<<1, kMaxCfgs, 0, st>>>(a);
+  finish_kernel<<<1, kFinishThreads, 0, st>>>(a);
   return launch_status();
 }

@@ -77,15 +77,24 @@ __device__ __forceinline__ void load_q_tile(const ScoreArgs& a, int l, int h, in
   }
 }
 
-// Stage of 64 keys starting at t0 into LDS (zeros beyond T).
-__device__ __forceinline__ void stage_keys(const ScoreArgs& a, const uint16_t* kbase, int t0, uint16_t* lds) {
+// A stage of 64 keys (zeros beyond T): global -> registers, then registers -> LDS, so that the next
+// stage's loads are in flight while the current one is consumed.
+constexpr int kStageVecs = (kStageKeys * 16) / kThreads;  // 16-byte pieces per thread and stage
+__device__ __forceinline__ void fetch_stage(const ScoreArgs& a, const uint16_t* kbase, int t0, uint4 v[kStageVecs]) {
 #pragma unroll
-  for (int i = 0; i < (kStageKeys * 16) / kThreads; ++i) {
+  for (int i = 0; i < kStageVecs; ++i) {
     const int idx = threadIdx.x + i * kThreads;
     const int key = idx >> 4, part = idx & 15;
-    uint4 v = make_uint4(0, 0, 0, 0);
-    if (t0 + key < a.T) v = *reinterpret_cast<const uint4*>(kbase + static_cast<int64_t>(t0 + key) * a.k_st + part * 8);
-    *reinterpret_cast<uint4*>(lds + key * kPitch + part * 8) = v;
+    v[i] = make_uint4(0, 0, 0, 0);
+    if (t0 + key < a.T) v[i] = load_stream16(kbase + static_cast<int64_t>(t0 + key) * a.k_st + part * 8);
+  }
+}
+__device__ __forceinline__ void commit_stage(const uint4 v[kStageVecs], uint16_t* lds) {
+#pragma unroll
+  for (int i = 0; i < kStageVecs; ++i) {
+    const int idx = threadIdx.x + i * kThreads;
+    const int key = idx >> 4, part = idx & 15;
+    *reinterpret_cast<uint4*>(lds + key * kPitch + part * 8) = v[i];
   }
 }
 
@@ -99,9 +108,9 @@ __device__ __forceinline__ void load_k_operand(const uint16_t* lds, int sub, int
 __device__ __forceinline__ int acc_row(int lane, int v) { return (lane >> 5) * 4 + (v >> 2) * 8 + (v & 3); }
 
 template <int QT, bool PASS_B>
-__global__ __launch_bounds__(kThreads) void score_kernel(const ScoreArgs a) {
+__global__ __launch_bounds__(kThreads, 2) void score_kernel(const ScoreArgs a) {
   __shared__ __attribute__((aligned(16))) uint16_t kstage[kStageKeys * kPitch];
-  __shared__ float bias_s[PASS_B ? kMaxRows : 1];
+  __shared__ __attribute__((aligned(16))) float bias_s[PASS_B ? kMaxRows : 4];
   __shared__ float colsum_s[PASS_B ? kWavesPerBlock * kStageKeys : 1];
 
   const int lane = threadIdx.x & 63;
@@ -147,10 +156,13 @@ __global__ __launch_bounds__(kThreads) void score_kernel(const ScoreArgs a) {
     qpos[i] = win0 + (r % a.W);
   }
 
+  uint4 pre[kStageVecs];
+  fetch_stage(a, kbase, t_begin, pre);
   for (int t0 = t_begin; t0 < t_end; t0 += kStageKeys) {
     __syncthreads();  // previous stage fully consumed
-    stage_keys(a, kbase, t0, kstage);
+    commit_stage(pre, kstage);
     __syncthreads();
+    if (t0 + kStageKeys < t_end) fetch_stage(a, kbase, t0 + kStageKeys, pre);
     const bool need_mask = (a.causal && t0 + kStageKeys > win0 + 1) || (t0 + kStageKeys > a.T);
 
 #pragma unroll
@@ -168,26 +180,32 @@ __global__ __launch_bounds__(kThreads) void score_kernel(const ScoreArgs a) {
         if constexpr (!PASS_B) {
 #pragma unroll
           for (int ks = 0; ks < 8; ++ks) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kop[ks], q[i][ks], acc, 0, 0, 0);
-          // acc[v] = logit(key tk0 + acc_row(v), query column lane%32)
-          float s[16];
-          float tmax = -INFINITY;
+          // acc[v] = raw dot product of key tk0 + acc_row(v) with query column lane%32
+          if (need_mask) {
 #pragma unroll
-          for (int v = 0; v < 16; ++v) {
-            s[v] = acc[v] * a.scale2;
-            if (need_mask) {
+            for (int v = 0; v < 16; ++v) {
               const int t = tk0 + acc_row(lane, v);
-              if (t >= a.T || (a.causal && t > qpos[i])) s[v] = -INFINITY;
+              if (t >= a.T || (a.causal && t > qpos[i])) acc[v] = -INFINITY;
             }
-            tmax = fmaxf(tmax, s[v]);
           }
-          const float m_new = fmaxf(run_m[i], tmax);
+          float tmax = acc[0];
+#pragma unroll
+          for (int v = 1; v < 16; ++v) tmax = fmaxf(tmax, acc[v]);
+          const float m_new = fmaxf(run_m[i], tmax * a.scale2);   // scale2 > 0: max commutes with it
           const float m_safe = (m_new == -INFINITY) ? 0.0f : m_new;
           float z = run_z[i] * __builtin_amdgcn_exp2f(run_m[i] - m_safe);
 #pragma unroll
-          for (int v = 0; v < 16; ++v) z += __builtin_amdgcn_exp2f(s[v] - m_safe);
+          for (int v = 0; v < 16; ++v) z += __builtin_amdgcn_exp2f(fmaf(acc[v], a.scale2, -m_safe));
           run_m[i] = m_new;
           run_z[i] = z;
         } else {
+          // bias of the 16 accumulator rows this lane holds: 4 runs of 4 consecutive rows
+          float bias[16];
+#pragma unroll
+          for (int g = 0; g < 4; ++g) {
+            const float4 b = *reinterpret_cast<const float4*>(bias_s + qt * 32 + g * 8 + (lane >> 5) * 4);
+            bias[4 * g + 0] = b.x; bias[4 * g + 1] = b.y; bias[4 * g + 2] = b.z; bias[4 * g + 3] = b.w;
+          }
 #pragma unroll
           for (int ks = 0; ks < 8; ++ks) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(q[i][ks], kop[ks], acc, 0, 0, 0);
           // acc[v] = logit(query row qt*32 + acc_row(v), key column tk0 + lane%32)
@@ -195,7 +213,7 @@ __global__ __launch_bounds__(kThreads) void score_kernel(const ScoreArgs a) {
 #pragma unroll
           for (int v = 0; v < 16; ++v) {
             const int r = qt * 32 + acc_row(lane, v);
-            float p = __builtin_amdgcn_exp2f(fmaf(acc[v], a.scale2, -bias_s[r]));
+            float p = __builtin_amdgcn_exp2f(fmaf(acc[v], a.scale2, -bias[v]));
             if (need_mask && a.causal && t > win0 + (r % a.W)) p = 0.0f;
             col += p;
           }

@@ -10,8 +10,10 @@
 // earlier elements above tau) + min(number of earlier elements equal to tau, quota), so ties at
 // the threshold go to the lowest indices.  Integer compares only: the result is exact.
 //
-// The row is re-read from global memory in every pass; after the first pass it is served by L2
-// (a row is at most 512 KiB at T = 131072).
+// Rows of up to 16384 scores are read from HBM exactly once and stay in registers (16 keys per
+// thread) through all passes.  Longer rows are processed in 16384-element spans that are re-read
+// (from L2 after the first pass) with the next span's loads issued before the current span is
+// consumed.  Every wave redoes the 256-bin digit search itself, so a pass costs two block barriers.
 
 #include "kvp_internal.h"
 
@@ -22,50 +24,76 @@ constexpr int kThreads = 1024;
 constexpr int kWaves = kThreads / kWave;
 constexpr int kCopies = 32;
 constexpr int kBins = 256;
-constexpr int kPerThread = 4;                       // consecutive elements per thread per chunk
-constexpr int kChunk = kThreads * kPerThread;       // 4096 elements
+constexpr int kItems = 4;                           // float4 items per thread per span
+constexpr int kChunk = kThreads * 4;                // elements covered by one item of all threads
+constexpr int kSpan = kChunk * kItems;              // 16384 elements
 
 // IEEE order -> unsigned order; -0.0 is folded onto +0.0 so that they tie, as with operator>.
+// Key 0 would be a negative NaN (out of contract): it marks slots beyond the end of the row and
+// sorts below every real score.
 __device__ __forceinline__ uint32_t to_key(float f) {
   uint32_t u = __float_as_uint(f);
   u = (u == 0x80000000u) ? 0u : u;
   return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
 }
 
-__device__ __forceinline__ void load4(const float* row, int64_t i, int64_t T, bool vec, uint32_t key[kPerThread],
-                                      bool valid[kPerThread]) {
-  if (vec && i + kPerThread <= T) {
-    const float4 v = *reinterpret_cast<const float4*>(row + i);
-    key[0] = to_key(v.x); key[1] = to_key(v.y); key[2] = to_key(v.z); key[3] = to_key(v.w);
+struct Span {
+  uint32_t key[kItems][4];
+};
+
+// Element index of (item c, thread tid, lane element e) inside a span: c * 4096 + tid * 4 + e.
+__device__ __forceinline__ void load_span(const float* row, int64_t base, int64_t T, bool vec, Span& s) {
 #pragma unroll
-    for (int e = 0; e < kPerThread; ++e) valid[e] = true;
-  } else {
+  for (int c = 0; c < kItems; ++c) {
+    const int64_t i = base + c * kChunk + static_cast<int64_t>(threadIdx.x) * 4;
+    if (vec && i + 4 <= T) {
+      const float4 v = *reinterpret_cast<const float4*>(row + i);
+      s.key[c][0] = to_key(v.x); s.key[c][1] = to_key(v.y); s.key[c][2] = to_key(v.z); s.key[c][3] = to_key(v.w);
+    } else {
 #pragma unroll
-    for (int e = 0; e < kPerThread; ++e) {
-      valid[e] = i + e < T;
-      key[e] = valid[e] ? to_key(row[i + e]) : 0u;
+      for (int e = 0; e < 4; ++e) s.key[c][e] = (i + e < T) ? to_key(row[i + e]) : 0u;
     }
   }
 }
 
-// inclusive scan across the 64 lanes of a wave
-__device__ __forceinline__ uint32_t wave_inclusive_scan(uint32_t v) {
-  const int lane = threadIdx.x & (kWave - 1);
+__device__ __forceinline__ void histogram_span(const Span& s, uint32_t mask, uint32_t prefix, int shift, uint32_t* hist) {
+  const int copy = threadIdx.x & (kCopies - 1);
 #pragma unroll
-  for (int off = 1; off < kWave; off <<= 1) {
-    const uint32_t n = __shfl_up(v, off, kWave);
-    if (lane >= off) v += n;
-  }
-  return v;
+  for (int c = 0; c < kItems; ++c)
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const uint32_t key = s.key[c][e];
+      // (end-of-row slots, key 0, fall into the lowest bin below every real score: harmless)
+      if ((key & mask) == prefix) atomicAdd(&hist[((key >> shift) & 0xffu) * kCopies + copy], 1u);
+    }
 }
 
-__global__ __launch_bounds__(kThreads) void select_topk_kernel(const float* __restrict__ scores, int64_t T,
-                                                               int64_t row_stride, int64_t k,
-                                                               int32_t* __restrict__ idx_out) {
+// inclusive scan across the 64 lanes of a wave with DPP row shifts and row broadcasts (no LDS traffic)
+template <int CTRL, int ROW_MASK, int BANK_MASK>
+__device__ __forceinline__ uint32_t dpp_or_zero(uint32_t v) {
+  return static_cast<uint32_t>(__builtin_amdgcn_update_dpp(0, static_cast<int>(v), CTRL, ROW_MASK, BANK_MASK, false));
+}
+__device__ __forceinline__ uint32_t wave_inclusive_scan(uint32_t v) {
+  uint32_t t = v;
+  t += dpp_or_zero<0x111, 0xf, 0xf>(v);   // row_shr:1
+  t += dpp_or_zero<0x112, 0xf, 0xf>(v);   // row_shr:2
+  t += dpp_or_zero<0x113, 0xf, 0xf>(v);   // row_shr:3
+  t += dpp_or_zero<0x114, 0xf, 0xe>(t);   // row_shr:4 into lanes 4..15 of each row
+  t += dpp_or_zero<0x118, 0xf, 0xc>(t);   // row_shr:8 into lanes 8..15 of each row
+  t += dpp_or_zero<0x142, 0xa, 0xf>(t);   // row_bcast:15 into rows 1 and 3
+  t += dpp_or_zero<0x143, 0xc, 0xf>(t);   // row_bcast:31 into rows 2 and 3
+  return t;
+}
+
+// RESIDENT: T <= kSpan, the whole row lives in registers.
+template <bool RESIDENT>
+__global__ __launch_bounds__(kThreads, RESIDENT ? 8 : 4) void select_topk_kernel(const float* __restrict__ scores,
+                                                                                 int64_t T, int64_t row_stride,
+                                                                                 int64_t k,
+                                                                                 int32_t* __restrict__ idx_out) {
   __shared__ uint32_t hist[kBins * kCopies];
   __shared__ uint32_t cnt[kBins];
-  __shared__ uint32_t s_prefix, s_krem;
-  __shared__ uint32_t wave_gt[kWaves], wave_eq[kWaves];
+  __shared__ uint32_t wave_tot[kItems][kWaves];
 
   const int tid = threadIdx.x;
   const int lane = tid & (kWave - 1);
@@ -73,32 +101,41 @@ __global__ __launch_bounds__(kThreads) void select_topk_kernel(const float* __re
   const float* row = scores + static_cast<int64_t>(blockIdx.x) * row_stride;
   int32_t* out = idx_out + static_cast<int64_t>(blockIdx.x) * k;
   const bool vec = ((reinterpret_cast<uintptr_t>(row) & 15u) == 0);
+  constexpr bool resident = RESIDENT;
+
+  Span cur;
+  load_span(row, 0, T, vec, cur);
+  for (int i = tid; i < kBins * kCopies; i += kThreads) hist[i] = 0;
+  __syncthreads();
 
   uint32_t prefix = 0, mask = 0, krem = static_cast<uint32_t>(k);
-
   for (int pass = 0; pass < 4; ++pass) {
     const int shift = 24 - 8 * pass;
-    for (int i = tid; i < kBins * kCopies; i += kThreads) hist[i] = 0;
-    __syncthreads();
-    for (int64_t base = 0; base < T; base += kChunk) {
-      uint32_t key[kPerThread];
-      bool valid[kPerThread];
-      load4(row, base + static_cast<int64_t>(tid) * kPerThread, T, vec, key, valid);
-#pragma unroll
-      for (int e = 0; e < kPerThread; ++e)
-        if (valid[e] && (key[e] & mask) == prefix)
-          atomicAdd(&hist[((key[e] >> shift) & 0xffu) * kCopies + (lane & (kCopies - 1))], 1u);
+    if (resident) {
+      histogram_span(cur, mask, prefix, shift, hist);
+    } else {
+      for (int64_t base = 0; base < T; base += kSpan) {
+        Span nxt;
+        const int64_t nb = base + kSpan < T ? base + kSpan : 0;   // wrap: span 0 is needed again next
+        load_span(row, nb, T, vec, nxt);
+        histogram_span(cur, mask, prefix, shift, hist);
+        cur = nxt;
+      }
     }
     __syncthreads();
     if (tid < kBins) {
       uint32_t sum = 0;
 #pragma unroll
-      for (int c = 0; c < kCopies; ++c) sum += hist[tid * kCopies + ((c + tid) & (kCopies - 1))];
+      for (int c = 0; c < kCopies; ++c) {
+        const int slot = tid * kCopies + ((c + tid) & (kCopies - 1));
+        sum += hist[slot];
+        hist[slot] = 0;   // ready for the next pass
+      }
       cnt[tid] = sum;
     }
     __syncthreads();
-    if (wave == 0) {
-      // lane j owns digits 255-4j .. 252-4j (descending); find the digit holding the krem-th largest
+    {
+      // every wave: lane j owns digits 255-4j .. 252-4j (descending); find the digit of the krem-th largest
       uint32_t c4[4], local = 0;
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
@@ -107,71 +144,83 @@ __global__ __launch_bounds__(kThreads) void select_topk_kernel(const float* __re
       }
       const uint32_t incl = wave_inclusive_scan(local);
       uint32_t above = incl - local;  // elements in digits larger than this lane's
-      if (above < krem && krem <= incl) {
+      const bool mine = above < krem && krem <= incl;
+      uint32_t new_prefix = 0, new_krem = 0;
+      if (mine) {
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
           if (above < krem && krem <= above + c4[e]) {
-            s_prefix = prefix | (static_cast<uint32_t>(255 - 4 * lane - e) << shift);
-            s_krem = krem - above;
+            new_prefix = prefix | (static_cast<uint32_t>(255 - 4 * lane - e) << shift);
+            new_krem = krem - above;
           }
           above += c4[e];
         }
       }
+      const int src = __ffsll(static_cast<long long>(__builtin_amdgcn_ballot_w64(mine))) - 1;  // exactly one lane
+      prefix = static_cast<uint32_t>(__builtin_amdgcn_readlane(static_cast<int>(new_prefix), src));
+      krem = static_cast<uint32_t>(__builtin_amdgcn_readlane(static_cast<int>(new_krem), src));
     }
-    __syncthreads();
-    prefix = s_prefix;
-    krem = s_krem;
     mask |= 0xffu << shift;
-    __syncthreads();
   }
 
   // prefix is now the key of the k-th largest score, krem the quota of elements equal to it.
   const uint32_t tau = prefix;
   uint32_t gt_base = 0, eq_base = 0;
-  for (int64_t base = 0; base < T; base += kChunk) {
-    uint32_t key[kPerThread];
-    bool valid[kPerThread];
-    const int64_t i0 = base + static_cast<int64_t>(tid) * kPerThread;
-    load4(row, i0, T, vec, key, valid);
-    uint32_t gt = 0, eq = 0;
-#pragma unroll
-    for (int e = 0; e < kPerThread; ++e) {
-      gt += (valid[e] && key[e] > tau) ? 1u : 0u;
-      eq += (valid[e] && key[e] == tau) ? 1u : 0u;
+  for (int64_t base = 0; base < T; base += kSpan) {
+    Span nxt;
+    if (!resident) {
+      const int64_t nb = base + kSpan < T ? base + kSpan : 0;
+      load_span(row, nb, T, vec, nxt);
     }
-    const uint32_t gt_incl = wave_inclusive_scan(gt);
-    const uint32_t eq_incl = wave_inclusive_scan(eq);
-    if (lane == kWave - 1) {
-      wave_gt[wave] = gt_incl;
-      wave_eq[wave] = eq_incl;
+    // per item: (#greater, #equal) of this thread's 4 elements, packed 16 + 16 bits (a span holds
+    // at most 16384 elements), scanned across the block in element order
+    uint32_t mine[kItems], incl[kItems];
+#pragma unroll
+    for (int c = 0; c < kItems; ++c) {
+      uint32_t g = 0, q = 0;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        g += cur.key[c][e] > tau ? 1u : 0u;
+        q += cur.key[c][e] == tau ? 1u : 0u;
+      }
+      mine[c] = g | (q << 16);
+      incl[c] = wave_inclusive_scan(mine[c]);
+      if (lane == kWave - 1) wave_tot[c][wave] = incl[c];
     }
     __syncthreads();
-    uint32_t gt_before = gt_base + gt_incl - gt, eq_before = eq_base + eq_incl - eq;
-    uint32_t gt_total = 0, eq_total = 0;
+    uint32_t span_tot = 0;
 #pragma unroll
-    for (int w = 0; w < kWaves; ++w) {
-      const uint32_t g = wave_gt[w], q = wave_eq[w];
-      if (w < wave) {
-        gt_before += g;
-        eq_before += q;
-      }
-      gt_total += g;
-      eq_total += q;
-    }
+    for (int c = 0; c < kItems; ++c) {
+      uint32_t before = span_tot;            // all earlier items of the span
+      uint32_t item_tot = 0;
 #pragma unroll
-    for (int e = 0; e < kPerThread; ++e) {
-      if (!valid[e]) continue;
-      if (key[e] > tau) {
-        out[gt_before + min(eq_before, krem)] = static_cast<int32_t>(i0 + e);
-        ++gt_before;
-      } else if (key[e] == tau) {
-        if (eq_before < krem) out[gt_before + eq_before] = static_cast<int32_t>(i0 + e);
-        ++eq_before;
+      for (int w = 0; w < kWaves; ++w) {
+        const uint32_t t = wave_tot[c][w];
+        if (w < wave) before += t;
+        item_tot += t;
+      }
+      span_tot += item_tot;
+      before += incl[c] - mine[c];
+      uint32_t gt_before = gt_base + (before & 0xffffu), eq_before = eq_base + (before >> 16);
+      const int64_t i0 = base + c * kChunk + static_cast<int64_t>(tid) * 4;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const uint32_t key = cur.key[c][e];
+        if (key > tau) {
+          out[gt_before + min(eq_before, krem)] = static_cast<int32_t>(i0 + e);
+          ++gt_before;
+        } else if (key == tau) {
+          if (eq_before < krem) out[gt_before + eq_before] = static_cast<int32_t>(i0 + e);
+          ++eq_before;
+        }
       }
     }
-    gt_base += gt_total;
-    eq_base += eq_total;
-    __syncthreads();
+    gt_base += span_tot & 0xffffu;
+    eq_base += span_tot >> 16;
+    if (!resident) {
+      cur = nxt;
+      __syncthreads();   // wave_tot is rewritten by the next span
+    }
   }
 }
 
@@ -179,7 +228,11 @@ __global__ __launch_bounds__(kThreads) void select_topk_kernel(const float* __re
 
 void select_topk_launch(const float* scores, int64_t n_rows, int64_t T, int64_t row_stride, int64_t k,
                         int32_t* idx_out, hipStream_t st) {
-  select_topk_kernel<<<dim3(static_cast<unsigned>(n_rows)), kThreads, 0, st>>>(scores, T, row_stride, k, idx_out);
+  const dim3 grid(static_cast<unsigned>(n_rows));
+  if (T <= kSpan)
+    select_topk_kernel<true><<<grid, kThreads, 0, st>>>(scores, T, row_stride, k, idx_out);
+  else
+    select_topk_kernel<false><<<grid, kThreads, 0, st>>>(scores, T, row_stride, k, idx_out);
 }
 
 }  // namespace kvp
