@@ -1,0 +1,161 @@
+"""GPU parity at the benchmark's full sizes, in the launch configurations bench.py times.
+
+The oracle cannot redo a multi-GiB cache in seconds, so outputs are sampled: rows (for the
+row-independent quantizer), whole score rows (for the selector), single (layer, head) pairs (for
+the scores and the loss proxy), each recomputed by the oracle from the very same bf16 bytes.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import workloads
+from helpers import torch_bits
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def _kvp():
+    import paper_2512_14946_amd as kvp
+    return kvp
+
+
+def _say(*a):
+    print("[case]", *a, flush=True)
+
+
+def _sample_rows(L, T, H, n, seed):
+    rng = np.random.default_rng(seed)
+    ls, ts, hs = rng.integers(0, L, n), rng.integers(0, T, n), rng.integers(0, H, n)
+    # always include the corners and the last page
+    ls[:4], ts[:4], hs[:4] = [0, L - 1, 0, L - 1], [0, T - 1, T - 1, 0], [0, H - 1, 0, H - 1]
+    return ls, ts, hs
+
+
+@pytest.mark.parametrize("name", ["llama3_8b_int4_paged", "long_context_int2"])
+def test_quantize_dequantize_full_plane_sampled_rows(name):
+    kvp = _kvp()
+    c = workloads.CONFIGS[name]
+    L, T, H, D, bits, group, bs = c["L"], c["T"], c["H"], c["D"], c["bits"], c["group"], c["bs"]
+    _say("full plane", name, (L, T, H, D), bits, group)
+    K, _ = workloads.make_kv(L, T, H, D, seed=0, outlier_scale=c["outlier_scale"], device=DEV)
+    qp = kvp.alloc_qplane(L, T, H, D, bits, group, DEV, page=bs)
+    kvp.kvp_quantize(K, qp)
+    bt, nb = workloads.make_block_table(T, bs, seed=0, device=DEV)
+    pg = kvp.alloc_paged(L, T, H, D, bt, nb, bs)
+    kvp.kvp_dequantize_paged(qp, pg)
+    torch.cuda.synchronize()
+    ls, ts, hs = _sample_rows(L, T, H, 4096, seed=1)
+    li, ti, hi = (torch.from_numpy(x).to(DEV) for x in (ls, ts, hs))
+    rows = torch_bits(K[li, ti, hi])                                      # [n][D]
+    got_codes = qp.codes[li, ti, hi].cpu().numpy()
+    got_scales = qp.scales[li, ti, hi].cpu().numpy()
+    blocks = bt.long()[ti // bs]
+    got_rows = torch_bits(pg.pool[li, blocks, ti % bs, hi])
+    oc, os_ = oracle.quantize(rows.reshape(1, -1, 1, D), bits, group)
+    assert np.array_equal(got_codes, oc[0, :, 0])
+    assert np.array_equal(got_scales.view(np.uint32), os_[0, :, 0].view(np.uint32))
+    n = rows.shape[0]
+    ident = np.arange((n + bs - 1) // bs, dtype=np.int32)
+    od = oracle.dequantize_paged(oc, os_, bits, group, n, ident, len(ident), bs).reshape(-1, D)[:n]
+    assert np.array_equal(got_rows, od)
+    # properties that hold at any size: padding-free plane, every scale finite and non-negative
+    assert qp.Tp == T
+    assert bool(torch.isfinite(qp.scales).all()) and bool((qp.scales >= 0).all())
+
+
+def test_drop_then_quantize_70b_shape_sampled():
+    kvp = _kvp()
+    c = workloads.CONFIGS["llama3_70b_drop_int4"]
+    L, T, H, D, G, W = 16, c["T"], c["H"], c["D"], c["G"], c["W"]          # 16 of the 80 layers (same grid shape per layer)
+    _say("70B-shaped drop+quantize", (L, T, H, D), G, W)
+    K, _ = workloads.make_kv(L, T, H, D, seed=0, device=DEV)
+    Q = workloads.make_q(L, W, G * H, D, seed=0, device=DEV)
+    k = kvp.kvp_keep_count(c["keep_ratio"], T)
+    assert k == 4916
+    s = kvp.kvp_score_tokens(Q, K)
+    idx = kvp.kvp_select_topk(s.view(L * H, T), k)
+    qk = kvp.alloc_qplane(L, k, H, D, c["bits"], c["group"], DEV)
+    kvp.kvp_quantize(K, qk, keep_idx=idx.view(L, H, k))
+    torch.cuda.synchronize()
+    # scores of one (layer, head) pair against the oracle (M = 512 rows x 16384 keys)
+    l, h = 5, 3
+    ref = oracle.score_tokens(torch_bits(Q[l:l + 1, :, h * G:(h + 1) * G]), torch_bits(K[l:l + 1, :, h:h + 1]))[0, 0]
+    got = s[l, h].cpu().numpy()
+    fin = np.isfinite(ref)
+    assert np.array_equal(np.isfinite(got), fin)
+    assert np.all(np.abs(got[fin] - ref[fin]) <= 1e-2 * np.abs(ref[fin]) + 1e-4 * G * W / T)
+    # selection: bit-exact on the GPU's own score rows (sampled rows), keep-set size, window kept
+    s_np = s.view(L * H, T).cpu().numpy()
+    idx_np = idx.cpu().numpy()
+    for r in (0, 37, L * H - 1):
+        assert np.array_equal(idx_np[r], oracle.select_topk(s_np[r:r + 1], k)[0])
+    assert idx_np.shape == (L * H, k) and np.all(np.diff(idx_np, axis=1) > 0)
+    assert np.all(idx_np[:, -W:] == np.arange(T - W, T))
+    # gathered quantization: sampled slots hold the quantized source token
+    rng = np.random.default_rng(2)
+    n = 2048
+    ls, ss, hs = rng.integers(0, L, n), rng.integers(0, k, n), rng.integers(0, H, n)
+    tok = idx_np.reshape(L, H, k)[ls, hs, ss]
+    li, ti, hi, si = (torch.from_numpy(np.asarray(x)).to(DEV) for x in (ls, tok, hs, ss))
+    rows = torch_bits(K[li, ti.long(), hi])
+    oc, os_ = oracle.quantize(rows.reshape(1, -1, 1, D), c["bits"], c["group"])
+    assert np.array_equal(qk.codes[li, si, hi].cpu().numpy(), oc[0, :, 0])
+    assert np.array_equal(qk.scales[li, si, hi].cpu().numpy().view(np.uint32), os_[0, :, 0].view(np.uint32))
+    assert not bool(qk.codes[:, k:].any()) and not bool(qk.scales[:, k:].any())   # padding slots
+
+
+def test_long_context_select_full_rows():
+    kvp = _kvp()
+    c = workloads.CONFIGS["long_context_int2"]
+    rows, T = c["L"] * c["H"], c["T"]
+    k = kvp.kvp_keep_count(c["keep_ratio"], T)
+    _say("long select", rows, T, k)
+    s = workloads.make_scores(rows, T, seed=0, device=DEV)
+    s[:, T - c["W"]:] = float("inf")
+    s[3] = torch.round(s[3] * 8) / 8                                        # a row full of ties
+    idx = kvp.kvp_select_topk(s, k)
+    torch.cuda.synchronize()
+    s_np, idx_np = s.cpu().numpy(), idx.cpu().numpy()
+    for r in (0, 3, 57, rows - 1):
+        assert np.array_equal(idx_np[r], oracle.select_topk(s_np[r:r + 1], k)[0])
+    # every row: ascending, distinct, every kept score >= every dropped score
+    assert np.all(np.diff(idx_np, axis=1) > 0)
+    kept_min = np.take_along_axis(s_np, idx_np, axis=1).min(axis=1)
+    mask = np.ones_like(s_np, dtype=bool)
+    np.put_along_axis(mask, idx_np, False, axis=1)
+    dropped_max = np.where(mask, s_np, -np.inf).max(axis=1)
+    assert np.all(kept_min >= dropped_max)
+
+
+def test_utility_sweep_context_properties_and_sampled_head():
+    kvp = _kvp()
+    c = workloads.CONFIGS["utility_sweep"]
+    L, T, H, D, G, W = c["L"], c["T"], c["H"], c["D"], c["G"], c["W"]
+    _say("utility sweep context", (L, T, H, D))
+    K, V = workloads.make_kv(L, T, H, D, seed=0, device=DEV)
+    Q = workloads.make_q(L, W, G * H, D, seed=0, device=DEV)
+    ks = [kvp.kvp_keep_count(r, T) for r in c["keep_ratios"]] + [T]
+    assert ks == [2048, 4096, 6144, 8192]
+    variants = [(16, 0)] + [(b, g) for b in c["bits_set"] for g in c["group_set"]]
+    cfgs = [(b, g, kk) for (b, g) in variants for kk in ks]
+    loss, partial = kvp.kvp_eval_configs(Q, K, V, cfgs, want_partial=True)
+    torch.cuda.synchronize()
+    loss = loss.cpu().numpy().reshape(len(variants), len(ks))
+    assert loss[0, 3] == 0.0                                               # identity row
+    assert np.all(np.isfinite(loss)) and np.all(loss[1:] > 0)
+    assert np.all(np.diff(loss, axis=1) < 0)                                # keeping more tokens never hurts here
+    for gi in range(3):                                                     # fewer bits, larger loss
+        assert np.all(loss[1 + gi] < loss[4 + gi]) and np.all(loss[4 + gi] < loss[7 + gi])
+    p = partial.cpu().numpy()
+    assert np.allclose(np.sqrt(p[..., 0].sum(0) / p[..., 1].sum(0)), loss.ravel(), rtol=1e-4)
+    # one (layer, head) pair in the same launch shape (T = 8192, M = 128) against the oracle
+    sub = [(16, 0, T), (8, 128, T), (4, 64, 4096), (2, 32, 2048), (16, 0, 2048)]
+    l, h = 7, 2
+    Qs, Ks, Vs = Q[l:l + 1, :, h * G:(h + 1) * G], K[l:l + 1, :, h:h + 1], V[l:l + 1, :, h:h + 1]
+    got = kvp.kvp_eval_configs(Qs, Ks, Vs, sub)
+    torch.cuda.synchronize()
+    ref, _ = oracle.eval_configs(torch_bits(Qs), torch_bits(Ks), torch_bits(Vs), sub)
+    got = got.cpu().numpy()
+    assert np.all(np.abs(got - ref) <= 1e-2 * np.abs(ref) + 1e-5), (got, ref)
