@@ -249,6 +249,12 @@ def side_measurements(kvp, workloads, torch, dev, K8, V8):
         tq = _time_loop(torch, lambda: kvp.kvp_quantize(K8, qp), 5)
         td = _time_loop(torch, lambda: kvp.kvp_dequantize_paged(qp, pg), 5)
         alg = K8.numel() * 2 + qp.nbytes()
+        if name == "int4_g32":
+            ident = kvp.PagedKV(pg.pool, torch.arange(nb, dtype=torch.int32, device=dev), T)
+            ti = _time_loop(torch, lambda: kvp.kvp_dequantize_paged(qp, ident), 5)
+            ops["dequantize_contiguous_pages_int4_g32"] = {
+                "workload": "same plane, identity block table (pages not scattered)",
+                "dequantize_GBs_alg": round(alg / ti / 1e9, 1), "dequantize_frac_hbm": round(alg / ti / 1e9 / HBM_PEAK_GBS, 4)}
         ops[name] = {"workload": f"{L}x{H}x{D}x{T} plane", "quantize_GBs_alg": round(alg / tq / 1e9, 1),
                      "dequantize_GBs_alg": round(alg / td / 1e9, 1),
                      "quantize_frac_hbm": round(alg / tq / 1e9 / HBM_PEAK_GBS, 4),
@@ -305,7 +311,8 @@ def side_measurements(kvp, workloads, torch, dev, K8, V8):
     loss = torch.empty(len(cfgs), dtype=torch.float32, device=dev)
     t_ev = _time_loop(torch, lambda: kvp.kvp_eval_configs(Qe, Ke, Ve, cfgs, loss=loss, ws=ws), 2)
     M = c["G"] * c["W"]
-    tokens = sum(kk for (_, _, kk) in cfgs)
+    # work actually done: the reference pass plus one stream per codec, each over the largest keep-set
+    tokens = (1 + len(variants)) * max(ks)
     pv_flops = 2.0 * c["L"] * c["H"] * M * c["D"] * tokens
     ops["utility_sweep"] = {"workload": f"1 of {c['n_ctx']} contexts: {c['L']}x{c['H']}x{c['D']}x{c['T']}, {len(cfgs)} configs",
                             "eval_ms_per_context": round(t_ev * 1e3, 2), "configs_per_s": round(len(cfgs) / t_ev, 1),

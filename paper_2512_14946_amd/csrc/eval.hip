@@ -279,6 +279,7 @@ __global__ __launch_bounds__(kThreads) void attention_kernel(const EvalArgs a) {
           acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(*reinterpret_cast<const uint4*>(krow + ks * 16)),
                                                         q[ks], acc, 0, 0, 0);
         if (need_mask) {
+          asm volatile("" ::: "memory");  // keep this a real (block-uniform, rarely taken) branch
 #pragma unroll
           for (int vv = 0; vv < 16; ++vv)
             if (tok_s[acc_row(lane, vv)] > qpos) acc[vv] = -INFINITY;

@@ -25,6 +25,8 @@
 //          lane-private adds plus one exchange between half-waves and a 4-way sum across waves in LDS.
 // Every key chunk is owned by exactly one block: no atomics, deterministic output.
 
+#include <type_traits>
+
 #include "kvp_internal.h"
 
 namespace kvp {
@@ -108,7 +110,7 @@ __device__ __forceinline__ void load_k_operand(const uint16_t* lds, int sub, int
 __device__ __forceinline__ int acc_row(int lane, int v) { return (lane >> 5) * 4 + (v >> 2) * 8 + (v & 3); }
 
 template <int QT, bool PASS_B>
-__global__ __launch_bounds__(kThreads, 2) void score_kernel(const ScoreArgs a) {
+__global__ __launch_bounds__(kThreads, QT >= 3 ? 1 : 2) void score_kernel(const ScoreArgs a) {
   __shared__ __attribute__((aligned(16))) uint16_t kstage[kStageKeys * kPitch];
   __shared__ __attribute__((aligned(16))) float bias_s[PASS_B ? kMaxRows : 4];
   __shared__ float colsum_s[PASS_B ? kWavesPerBlock * kStageKeys : 1];
@@ -138,7 +140,9 @@ __global__ __launch_bounds__(kThreads, 2) void score_kernel(const ScoreArgs a) {
   }
 
   if constexpr (PASS_B) {
-    for (int r = threadIdx.x; r < a.Mpad; r += kThreads) bias_s[r] = a.bias[static_cast<int64_t>(lh) * a.Mpad + r];
+    // rows beyond M (padding of the last tile, tiles a wave does not own) get +inf: they contribute 0
+    for (int r = threadIdx.x; r < kMaxRows; r += kThreads)
+      bias_s[r] = r < a.Mpad ? a.bias[static_cast<int64_t>(lh) * a.Mpad + r] : INFINITY;
   }
 
   // pass A state: running max / sum of this lane's query column over this lane's keys
@@ -156,6 +160,88 @@ __global__ __launch_bounds__(kThreads, 2) void score_kernel(const ScoreArgs a) {
     qpos[i] = win0 + (r % a.W);
   }
 
+  // One 64-key stage.  The tiles (key sub-tile x query tile) are walked in a software pipeline: the
+  // eight MFMAs of tile n+1 are issued before the vector-ALU work of tile n, so a wave never waits
+  // for a matrix result.  MASKED stages (the causal window, the ragged end of the row) are a
+  // separate instantiation so that the common stage carries no mask arithmetic.
+  auto mfma_tile = [&](const bf16x8 kop[8], const bf16x8 qop[8]) {
+    floatx16 acc = {0};
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) {
+      if constexpr (PASS_B)
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qop[ks], kop[ks], acc, 0, 0, 0);  // rows = queries, lane = key
+      else
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kop[ks], qop[ks], acc, 0, 0, 0);  // rows = keys, lane = query
+    }
+    return acc;
+  };
+
+  auto stage = [&](auto masked_tag, int t0) {
+    constexpr bool MASKED = decltype(masked_tag)::value;
+    constexpr int NT = (kStageKeys / 32) * QT;
+    bf16x8 kop[8];
+    floatx16 acc[2];
+    load_k_operand(kstage, 0, lane, kop);
+    acc[0] = mfma_tile(kop, q[0]);
+    float col = 0.0f;  // pass B: this lane's key column
+#pragma unroll
+    for (int tt = 0; tt < NT; ++tt) {
+      const int sub = tt / QT, i = tt % QT;
+      if (tt + 1 < NT) {
+        if ((tt + 1) % QT == 0) load_k_operand(kstage, (tt + 1) / QT, lane, kop);
+        acc[(tt + 1) & 1] = mfma_tile(kop, q[(tt + 1) % QT]);
+      }
+      floatx16& c = acc[tt & 1];
+      const int tk0 = t0 + sub * 32;
+      const int qt = wave + i * kWavesPerBlock;
+      if constexpr (!PASS_B) {
+        // c[v] = raw dot product of key tk0 + acc_row(v) with query column lane%32
+        if constexpr (MASKED) {
+#pragma unroll
+          for (int v = 0; v < 16; ++v) {
+            const int t = tk0 + acc_row(lane, v);
+            if (t >= a.T || (a.causal && t > qpos[i])) c[v] = -INFINITY;
+          }
+        }
+        float tmax = c[0];
+#pragma unroll
+        for (int v = 1; v < 16; ++v) tmax = fmaxf(tmax, c[v]);
+        const float m_new = fmaxf(run_m[i], tmax * a.scale2);   // scale2 > 0: max commutes with it
+        const float m_safe = (m_new == -INFINITY) ? 0.0f : m_new;
+        float z = run_z[i] * __builtin_amdgcn_exp2f(run_m[i] - m_safe);
+#pragma unroll
+        for (int v = 0; v < 16; ++v) z += __builtin_amdgcn_exp2f(fmaf(c[v], a.scale2, -m_safe));
+        run_m[i] = m_new;
+        run_z[i] = z;
+      } else {
+        // c[v] = raw dot product of query row qt*32 + acc_row(v) with key column tk0 + lane%32
+        float bias[16];
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const float4 b4 = *reinterpret_cast<const float4*>(bias_s + qt * 32 + g * 8 + (lane >> 5) * 4);
+          bias[4 * g + 0] = b4.x; bias[4 * g + 1] = b4.y; bias[4 * g + 2] = b4.z; bias[4 * g + 3] = b4.w;
+        }
+        if constexpr (MASKED) {
+          const int t = tk0 + (lane & 31);
+          if (a.causal) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+              const int r = qt * 32 + acc_row(lane, v);
+              if (t > win0 + (r % a.W)) c[v] = -INFINITY;
+            }
+          }
+        }
+#pragma unroll
+        for (int v = 0; v < 16; ++v) col += __builtin_amdgcn_exp2f(fmaf(c[v], a.scale2, -bias[v]));
+        if (i == QT - 1) {
+          col += __shfl_xor(col, 32, 64);
+          if (lane < 32) colsum_s[wave * kStageKeys + sub * 32 + lane] = col;
+          col = 0.0f;
+        }
+      }
+    }
+  };
+
   uint4 pre[kStageVecs];
   fetch_stage(a, kbase, t_begin, pre);
   for (int t0 = t_begin; t0 < t_end; t0 += kStageKeys) {
@@ -164,66 +250,11 @@ __global__ __launch_bounds__(kThreads, 2) void score_kernel(const ScoreArgs a) {
     __syncthreads();
     if (t0 + kStageKeys < t_end) fetch_stage(a, kbase, t0 + kStageKeys, pre);
     const bool need_mask = (a.causal && t0 + kStageKeys > win0 + 1) || (t0 + kStageKeys > a.T);
+    if (need_mask)
+      stage(std::true_type{}, t0);
+    else
+      stage(std::false_type{}, t0);
 
-#pragma unroll
-    for (int sub = 0; sub < kStageKeys / 32; ++sub) {
-      bf16x8 kop[8];
-      load_k_operand(kstage, sub, lane, kop);
-      const int tk0 = t0 + sub * 32;
-      float col = 0.0f;  // pass B: this lane's key column
-
-#pragma unroll
-      for (int i = 0; i < QT; ++i) {
-        const int qt = wave + i * kWavesPerBlock;
-        if (qt >= n_qt) continue;  // wave-uniform
-        floatx16 acc = {0};
-        if constexpr (!PASS_B) {
-#pragma unroll
-          for (int ks = 0; ks < 8; ++ks) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kop[ks], q[i][ks], acc, 0, 0, 0);
-          // acc[v] = raw dot product of key tk0 + acc_row(v) with query column lane%32
-          if (need_mask) {
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-              const int t = tk0 + acc_row(lane, v);
-              if (t >= a.T || (a.causal && t > qpos[i])) acc[v] = -INFINITY;
-            }
-          }
-          float tmax = acc[0];
-#pragma unroll
-          for (int v = 1; v < 16; ++v) tmax = fmaxf(tmax, acc[v]);
-          const float m_new = fmaxf(run_m[i], tmax * a.scale2);   // scale2 > 0: max commutes with it
-          const float m_safe = (m_new == -INFINITY) ? 0.0f : m_new;
-          float z = run_z[i] * __builtin_amdgcn_exp2f(run_m[i] - m_safe);
-#pragma unroll
-          for (int v = 0; v < 16; ++v) z += __builtin_amdgcn_exp2f(fmaf(acc[v], a.scale2, -m_safe));
-          run_m[i] = m_new;
-          run_z[i] = z;
-        } else {
-          // bias of the 16 accumulator rows this lane holds: 4 runs of 4 consecutive rows
-          float bias[16];
-#pragma unroll
-          for (int g = 0; g < 4; ++g) {
-            const float4 b = *reinterpret_cast<const float4*>(bias_s + qt * 32 + g * 8 + (lane >> 5) * 4);
-            bias[4 * g + 0] = b.x; bias[4 * g + 1] = b.y; bias[4 * g + 2] = b.z; bias[4 * g + 3] = b.w;
-          }
-#pragma unroll
-          for (int ks = 0; ks < 8; ++ks) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(q[i][ks], kop[ks], acc, 0, 0, 0);
-          // acc[v] = logit(query row qt*32 + acc_row(v), key column tk0 + lane%32)
-          const int t = tk0 + (lane & 31);
-#pragma unroll
-          for (int v = 0; v < 16; ++v) {
-            const int r = qt * 32 + acc_row(lane, v);
-            float p = __builtin_amdgcn_exp2f(fmaf(acc[v], a.scale2, -bias[v]));
-            if (need_mask && a.causal && t > win0 + (r % a.W)) p = 0.0f;
-            col += p;
-          }
-        }
-      }
-      if constexpr (PASS_B) {
-        col += __shfl_xor(col, 32, 64);
-        if (lane < 32) colsum_s[wave * kStageKeys + sub * 32 + lane] = col;
-      }
-    }
     if constexpr (PASS_B) {
       __syncthreads();
       if (threadIdx.x < kStageKeys) {
