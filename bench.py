@@ -335,6 +335,31 @@ def profile_only(args, kvp, workloads, torch, dev, K, V, qK, pK, bt, nb):
         tmp = torch.empty_like(K)
         for _ in range(n):
             kvp.kvp_copy_bytes(tmp, K)
+    elif args.only in ("score", "select"):
+        c = workloads.CONFIGS["llama3_70b_drop_int4"]
+        Ls = 16
+        Kc, _ = workloads.make_kv(Ls, c["T"], c["H"], c["D"], seed=0, device=dev)
+        Qc = workloads.make_q(Ls, c["W"], c["G"] * c["H"], c["D"], seed=0, device=dev)
+        sc = torch.empty(Ls, c["H"], c["T"], dtype=torch.float32, device=dev)
+        ws = torch.empty(kvp.kvp_score_workspace_bytes(Ls, c["H"], c["G"] * c["H"], c["W"], c["T"]) + 16,
+                         dtype=torch.uint8, device=dev)
+        k = kvp.kvp_keep_count(c["keep_ratio"], c["T"])
+        idx = torch.empty(Ls * c["H"], k, dtype=torch.int32, device=dev)
+        kvp.kvp_score_tokens(Qc, Kc, sc, ws=ws)
+        for _ in range(n):
+            if args.only == "score":
+                kvp.kvp_score_tokens(Qc, Kc, sc, ws=ws)
+            else:
+                kvp.kvp_select_topk(sc.view(Ls * c["H"], c["T"]), k, idx)
+    elif args.only == "eval":
+        c = workloads.CONFIGS["utility_sweep"]
+        Ke, Ve = workloads.make_kv(c["L"], c["T"], c["H"], c["D"], seed=0, device=dev)
+        Qe = workloads.make_q(c["L"], c["W"], c["G"] * c["H"], c["D"], seed=0, device=dev)
+        ks = [kvp.kvp_keep_count(r, c["T"]) for r in c["keep_ratios"]] + [c["T"]]
+        variants = [(16, 0)] + [(b, g) for b in c["bits_set"] for g in c["group_set"]]
+        cfgs = [(b, g, kk) for (b, g) in variants for kk in ks]
+        for _ in range(n):
+            kvp.kvp_eval_configs(Qe, Ke, Ve, cfgs)
     else:
         raise SystemExit(f"unknown --only {args.only}")
     torch.cuda.synchronize()
