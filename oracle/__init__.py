@@ -54,6 +54,8 @@ def lib():
         _lib.oracle_score_tokens.restype = ctypes.c_int
         _lib.oracle_score_tokens.argtypes = [_p, _i64, _i64, _i64, _i64, _i64, _p, _i64, _i64, _i64, _i64,
                                              _i64, _i64, _i64, ctypes.c_int, ctypes.c_int, _p]
+        _lib.oracle_score_keys.restype = ctypes.c_int
+        _lib.oracle_score_keys.argtypes = [_p, _i64, _i64, _i64, _i64, _i64, _i64, _i64, ctypes.c_int, _p, _i64, _p]
         _lib.oracle_select_topk.restype = ctypes.c_int
         _lib.oracle_select_topk.argtypes = [_p, _i64, _i64, _i64, _i64, _p]
         _lib.oracle_eval_configs.restype = ctypes.c_int
@@ -170,6 +172,23 @@ def score_tokens(q: np.ndarray, k: np.ndarray, causal: bool = True, force_window
     _check(lib().oracle_score_tokens(_ptr(q), W, Hq, qsl, qst, qsh, _ptr(k), L, T, Hkv, D, ksl, kst, ksh,
                                      int(causal), int(force_window), _ptr(scores)), "score_tokens")
     return scores
+
+
+KNORM, KEYDIFF = 0, 1
+
+
+def score_keys(k: np.ndarray, method: int, tokens: np.ndarray | None = None) -> np.ndarray:
+    """k: uint16 [L][T][H][D] -> key-only importance f32 [L][H][T] (or [L][H][n] for the listed tokens)."""
+    k, ksl, kst, ksh = _view4(k)
+    L, T, H, D = k.shape
+    n = 0
+    if tokens is not None:
+        tokens = np.ascontiguousarray(tokens, dtype=np.int32)
+        n = len(tokens)
+    out = np.empty((L, H, n if tokens is not None else T), dtype=np.float32)
+    _check(lib().oracle_score_keys(_ptr(k), L, T, H, D, ksl, kst, ksh, int(method), _ptr(tokens), n, _ptr(out)),
+           "score_keys")
+    return out
 
 
 def select_topk(scores: np.ndarray, k: int) -> np.ndarray:

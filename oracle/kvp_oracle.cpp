@@ -22,6 +22,8 @@
 //   oracle_quantize / oracle_dequantize_paged / oracle_select_topk: pinned by
 //     hand-exact examples, exact rational arithmetic, invariants and brute
 //     force (tests/test_oracle_*.py).
+//   oracle_score_keys (knorm, keydiff): pinned by closed forms (3-4-5 norms, identical / orthogonal /
+//     antipodal keys), scale invariance and a library float64 normalize + matmul.
 //   oracle_score_tokens / oracle_eval_configs: pinned by closed forms,
 //     invariants, a library float64 softmax on tiny shapes and an independent
 //     tiny brute force; the absolute values on random data are otherwise
@@ -417,6 +419,55 @@ int oracle_eval_configs(const uint16_t* q, int64_t W, int64_t Hq, int64_t q_sl, 
   }
   for (int32_t ci = 0; ci < n_cfgs; ++ci)
     loss[ci] = static_cast<float>(std::sqrt(num[static_cast<size_t>(ci)] / den));
+  return 0;
+}
+
+// Key-only token importance of the paper's two other token-dropping methods (Evaluation, Baselines):
+//   method 0, knorm:   "computes the L2 norm of the key cache, and drops those with low L2 norm"
+//                      score[t] = ||k_t||_2                              (keep the largest)
+//   method 1, keydiff: "computes the average cosine similarity of every token to all other tokens,
+//                      and drops the tokens whose similarities are high"
+//                      score[t] = - mean over t' != t of cos(k_t, k_t')  (keep the largest)
+// written out as the plain definitions (keydiff is the O(T^2 D) double loop).  A zero key has cosine
+// 0 with everything; T == 1 gives score 0.  With `tokens` (n of them) only those tokens are scored
+// (out has n entries per (layer, head)); otherwise all T (out is [L][H][T]).
+int oracle_score_keys(const uint16_t* k, int64_t L, int64_t T, int64_t H, int64_t D, int64_t k_sl, int64_t k_st,
+                      int64_t k_sh, int method, const int32_t* tokens, int64_t n, float* out) {
+  if (!k || !out || L < 0 || T <= 0 || H <= 0 || D <= 0 || (method != 0 && method != 1)) return -1;
+  const View kv{k, k_sl, k_st, k_sh};
+  const int64_t n_out = tokens ? n : T;
+  std::vector<double> norm(static_cast<size_t>(T));
+  for (int64_t l = 0; l < L; ++l)
+    for (int64_t h = 0; h < H; ++h) {
+      for (int64_t t = 0; t < T; ++t) {
+        double ss = 0.0;
+        const uint16_t* r = kv.row(l, t, h);
+        for (int64_t c = 0; c < D; ++c) ss += static_cast<double>(bf16_to_f32(r[c])) * bf16_to_f32(r[c]);
+        norm[static_cast<size_t>(t)] = std::sqrt(ss);
+      }
+      for (int64_t i = 0; i < n_out; ++i) {
+        const int64_t t = tokens ? tokens[i] : i;
+        if (t < 0 || t >= T) return -1;
+        double score;
+        if (method == 0) {
+          score = norm[static_cast<size_t>(t)];
+        } else {
+          double acc = 0.0;
+          const uint16_t* a = kv.row(l, t, h);
+          for (int64_t u = 0; u < T; ++u) {
+            if (u == t) continue;
+            const double nn = norm[static_cast<size_t>(t)] * norm[static_cast<size_t>(u)];
+            if (nn == 0.0) continue;
+            const uint16_t* b = kv.row(l, u, h);
+            double dot = 0.0;
+            for (int64_t c = 0; c < D; ++c) dot += static_cast<double>(bf16_to_f32(a[c])) * bf16_to_f32(b[c]);
+            acc += dot / nn;
+          }
+          score = T > 1 ? -acc / static_cast<double>(T - 1) : 0.0;
+        }
+        out[(l * H + h) * n_out + i] = static_cast<float>(score);
+      }
+    }
   return 0;
 }
 
