@@ -260,6 +260,18 @@ def side_measurements(kvp, workloads, torch, dev, K8, V8):
                      "quantize_frac_hbm": round(alg / tq / 1e9 / HBM_PEAK_GBS, 4),
                      "dequantize_frac_hbm": round(alg / td / 1e9 / HBM_PEAK_GBS, 4)}
         del qp, pg
+    # --- key-only importance scores (knorm, keydiff) on the resident K plane ---
+    sc8 = torch.empty(L, H, T, dtype=torch.float32, device=dev)
+    wsk = torch.empty(kvp.kvp_score_keys_workspace_bytes(L, H, T, kvp.KVP_SCORE_KEYDIFF) + 16, dtype=torch.uint8, device=dev)
+    tn = _time_loop(torch, lambda: kvp.kvp_score_keys(K8, kvp.KVP_SCORE_KNORM, sc8), 5)
+    tk = _time_loop(torch, lambda: kvp.kvp_score_keys(K8, kvp.KVP_SCORE_KEYDIFF, sc8, ws=wsk), 5)
+    kb = K8.numel() * 2
+    ops["key_scores"] = {"workload": f"{L}x{H}x{D}x{T} K plane",
+                         "knorm_ms": round(tn * 1e3, 3), "knorm_GBs_alg": round((kb + sc8.numel() * 4) / tn / 1e9, 1),
+                         "knorm_frac_hbm": round((kb + sc8.numel() * 4) / tn / 1e9 / HBM_PEAK_GBS, 4),
+                         "keydiff_ms": round(tk * 1e3, 3), "keydiff_GBs_alg": round((2 * kb + sc8.numel() * 4) / tk / 1e9, 1),
+                         "keydiff_frac_hbm": round((2 * kb + sc8.numel() * 4) / tk / 1e9 / HBM_PEAK_GBS, 4)}
+    del sc8, wsk
     # --- 70B-shaped drop + quantize pipeline on a 16-layer slice of the resident planes' shape ---
     c = workloads.CONFIGS["llama3_70b_drop_int4"]
     Ls = 16

@@ -121,6 +121,19 @@ int32_t kvp_score_tokens(const kvp_view* q_win, const kvp_view* k, int32_t causa
                          float* scores, void* ws, size_t ws_bytes, void* stream);
 size_t kvp_score_workspace_bytes(int64_t L, int64_t Hkv, int64_t Hq, int64_t W, int64_t T);
 
+/* Key-only token importance of the paper's two other token-dropping methods
+ * (Evaluation, Baselines): knorm scores a token by the L2 norm of its key (low
+ * norms are dropped); keydiff by the average cosine similarity of its key to
+ * the keys of all other tokens (similar tokens are dropped).  scores (device
+ * fp32 [L][H][T]) are "keep the largest" scores for kvp_select_topk:
+ *     KVP_SCORE_KNORM    scores[l][h][t] = ||k_t||_2
+ *     KVP_SCORE_KEYDIFF  scores[l][h][t] = - mean over t' != t of cos(k_t, k_t')
+ * A zero key has cosine 0 with every key; T == 1 gives 0.  bf16 input, fp32
+ * arithmetic.  No window is forced.  knorm needs no workspace. */
+enum { KVP_SCORE_KNORM = 0, KVP_SCORE_KEYDIFF = 1 };
+int32_t kvp_score_keys(const kvp_view* k, int32_t method, float* scores, void* ws, size_t ws_bytes, void* stream);
+size_t kvp_score_keys_workspace_bytes(int64_t L, int64_t H, int64_t T, int32_t method);
+
 /* Per-row top-k keep-set (Evaluation, Baselines: tokens "with low
  * cross-attention scores" are dropped; IMPRESS keeps the top X%).  For each
  * of n_rows rows of T fp32 scores (row_stride floats apart): the indices of the

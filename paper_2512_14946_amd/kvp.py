@@ -62,6 +62,10 @@ def _load(path: str = _LIB_PATH):
     lib.kvp_score_tokens.argtypes = [P(_View), P(_View), _i32, _i32, _vp, _vp, _sz, _vp]
     lib.kvp_score_workspace_bytes.restype = _sz
     lib.kvp_score_workspace_bytes.argtypes = [_i64] * 5
+    lib.kvp_score_keys.restype = _i32
+    lib.kvp_score_keys.argtypes = [P(_View), _i32, _vp, _vp, _sz, _vp]
+    lib.kvp_score_keys_workspace_bytes.restype = _sz
+    lib.kvp_score_keys_workspace_bytes.argtypes = [_i64, _i64, _i64, _i32]
     lib.kvp_select_topk.restype = _i32
     lib.kvp_select_topk.argtypes = [_vp, _i64, _i64, _i64, _i64, _vp, _vp, _sz, _vp]
     lib.kvp_select_workspace_bytes.restype = _sz
@@ -248,6 +252,29 @@ def kvp_score_tokens(q_win: torch.Tensor, k: torch.Tensor, scores: torch.Tensor 
     qv, kv = _view(q_win), _view(k)
     _check(_lib.kvp_score_tokens(ctypes.byref(qv), ctypes.byref(kv), int(causal), int(force_window),
                                  scores.data_ptr(), wp, wb, _stream(stream)), "kvp_score_tokens")
+    return scores
+
+
+KVP_SCORE_KNORM, KVP_SCORE_KEYDIFF = 0, 1
+
+
+def kvp_score_keys_workspace_bytes(L: int, H: int, T: int, method: int) -> int:
+    return int(_lib.kvp_score_keys_workspace_bytes(L, H, T, method))
+
+
+def kvp_score_keys(k: torch.Tensor, method: int, scores: torch.Tensor | None = None,
+                   ws: torch.Tensor | None = None, stream=None) -> torch.Tensor:
+    """k bf16 [L][T][H][D] -> key-only importance f32 [L][H][T] (knorm or keydiff), keep the largest."""
+    _need_cuda(k, scores, ws)
+    L, T, H, _ = k.shape
+    if scores is None:
+        scores = torch.empty(L, H, T, dtype=torch.float32, device=k.device)
+    if scores.dtype != torch.float32 or not scores.is_contiguous() or tuple(scores.shape) != (L, H, T):
+        raise ValueError("scores must be contiguous float32 [L][H][T]")
+    ws, wp, wb = _workspace(ws, kvp_score_keys_workspace_bytes(L, H, T, method), k.device)
+    kv = _view(k)
+    _check(_lib.kvp_score_keys(ctypes.byref(kv), int(method), scores.data_ptr(), wp, wb, _stream(stream)),
+           "kvp_score_keys")
     return scores
 
 
