@@ -160,6 +160,40 @@ int32_t kvp_eval_configs(const kvp_view* q_win, const kvp_view* k, const kvp_vie
                          int32_t n_cfgs, float* loss, float* partial, void* ws, size_t ws_bytes, void* stream);
 size_t kvp_eval_workspace_bytes(int64_t L, int64_t Hkv, int64_t Hq, int64_t W, int64_t T, int32_t n_cfgs);
 
+/* ---- policy layer on the HOST (all pointers below are host pointers; no kernel is launched) ----
+ *
+ * Utility of a stored configuration (System design, "Utility function"):
+ *     Util(config, tier) = (alpha * quality - TTFT) * frequency,  TTFT = bytes / tier bandwidth
+ * quality is 1 - loss of kvp_eval_configs (or any quality score in [0, 1]). */
+typedef struct {
+  double capacity_bytes;        /* negative = unbounded */
+  double bandwidth_bytes_per_s; /* loading bandwidth towards the GPU, > 0 */
+} kvp_tier;
+
+/* util[tier][cfg] for one context.  quality, bytes: [n_cfg]; util: [n_tiers][n_cfg]. */
+int32_t kvp_utility_table(const double* quality, const double* bytes, int32_t n_cfg, const kvp_tier* tiers,
+                          int32_t n_tiers, double alpha, double frequency, double* util);
+
+enum { KVP_OP_INSERT = 0, KVP_OP_COMPRESS = 1, KVP_OP_EVICT = 2 };
+typedef struct {
+  int32_t ctx, cfg, tier, op; /* context, its configuration after the operation, the tier it is on after it */
+} kvp_policy_op;
+
+/* Greedy placement (appendix, Policy Optimizer; "Eviction-compression configuration selection
+ * module").  Context `incoming` enters tier 0 with its highest-quality configuration (fewest
+ * bytes, then lowest index, among equals).  Then every bounded tier, first to last, is brought
+ * under its capacity by repeatedly applying the operation with the least utility drop among: re-
+ * compressing a cache on the tier to a configuration with fewer bytes, or evicting it unchanged to
+ * the next tier (ties: lowest context, compress before evict, lowest configuration).
+ * bytes, quality: [n_ctx][n_cfg]; frequency: [n_ctx]; ctx_tier (-1 = not stored) and ctx_cfg:
+ * [n_ctx], updated in place.  The operations are written to ops (at most max_ops) and counted in
+ * *n_ops.  KVP_ERR_SHAPE if the last tier is bounded and cannot be made to fit;
+ * KVP_ERR_WORKSPACE if max_ops is too small (the state then reflects the operations written). */
+int32_t kvp_policy_insert(int32_t n_ctx, int32_t n_cfg, const double* bytes, const double* quality,
+                          const double* frequency, const kvp_tier* tiers, int32_t n_tiers, double alpha,
+                          int32_t* ctx_tier, int32_t* ctx_cfg, int32_t incoming, kvp_policy_op* ops,
+                          int32_t max_ops, int32_t* n_ops);
+
 /* Host helper: tokens kept at a keep-ratio = ceil(ratio * T) in double, clamped to [1, T]. */
 int64_t kvp_keep_count(double ratio, int64_t T);
 

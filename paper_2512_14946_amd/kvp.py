@@ -39,6 +39,14 @@ class _QPlane(ctypes.Structure):
                 ("L", _i64), ("T", _i64), ("Tp", _i64), ("H", _i64), ("D", _i64)]
 
 
+class _Tier(ctypes.Structure):
+    _fields_ = [("capacity_bytes", ctypes.c_double), ("bandwidth_bytes_per_s", ctypes.c_double)]
+
+
+class _PolicyOp(ctypes.Structure):
+    _fields_ = [("ctx", _i32), ("cfg", _i32), ("tier", _i32), ("op", _i32)]
+
+
 class _Config(ctypes.Structure):
     _fields_ = [("bits", _i32), ("group", _i32), ("keep_k", _i64)]
 
@@ -74,6 +82,11 @@ def _load(path: str = _LIB_PATH):
     lib.kvp_eval_configs.argtypes = [P(_View), P(_View), P(_View), P(_Config), _i32, _vp, _vp, _vp, _sz, _vp]
     lib.kvp_eval_workspace_bytes.restype = _sz
     lib.kvp_eval_workspace_bytes.argtypes = [_i64] * 5 + [_i32]
+    lib.kvp_utility_table.restype = _i32
+    lib.kvp_utility_table.argtypes = [_vp, _vp, _i32, P(_Tier), _i32, ctypes.c_double, ctypes.c_double, _vp]
+    lib.kvp_policy_insert.restype = _i32
+    lib.kvp_policy_insert.argtypes = [_i32, _i32, _vp, _vp, _vp, P(_Tier), _i32, ctypes.c_double, _vp, _vp, _i32,
+                                      P(_PolicyOp), _i32, P(_i32)]
     lib.kvp_keep_count.restype = _i64
     lib.kvp_keep_count.argtypes = [ctypes.c_double, _i64]
     lib.kvp_copy_bytes.restype = _i32
@@ -324,6 +337,46 @@ def kvp_eval_configs(q_win: torch.Tensor, k: torch.Tensor, v: torch.Tensor, cfgs
                                  partial.data_ptr() if partial is not None else None, wp, wb, _stream(stream)),
            "kvp_eval_configs")
     return (loss, partial) if partial is not None else loss
+
+
+KVP_OP_INSERT, KVP_OP_COMPRESS, KVP_OP_EVICT = 0, 1, 2
+
+
+def _tiers(tiers):
+    return (_Tier * len(tiers))(*[_Tier(float(c), float(b)) for c, b in tiers])
+
+
+def kvp_utility_table(quality, nbytes, tiers, alpha: float, frequency: float = 1.0):
+    """Host call.  quality, nbytes: sequences [n_cfg]; tiers: [(capacity_bytes, bandwidth)] -> util [n_tiers][n_cfg]."""
+    import numpy as np
+    q = np.ascontiguousarray(quality, dtype=np.float64)
+    b = np.ascontiguousarray(nbytes, dtype=np.float64)
+    out = np.empty((len(tiers), len(q)), dtype=np.float64)
+    _check(_lib.kvp_utility_table(q.ctypes.data, b.ctypes.data, len(q), _tiers(tiers), len(tiers), float(alpha),
+                                  float(frequency), out.ctypes.data), "kvp_utility_table")
+    return out
+
+
+def kvp_policy_insert(nbytes, quality, frequency, tiers, alpha: float, ctx_tier, ctx_cfg, incoming: int,
+                      max_ops: int | None = None):
+    """Host call.  nbytes, quality: [n_ctx][n_cfg]; ctx_tier / ctx_cfg: int32 numpy arrays updated in place.
+    Returns the list of (ctx, cfg, tier, op)."""
+    import numpy as np
+    b = np.ascontiguousarray(nbytes, dtype=np.float64)
+    q = np.ascontiguousarray(quality, dtype=np.float64)
+    f = np.ascontiguousarray(frequency, dtype=np.float64)
+    n_ctx, n_cfg = b.shape
+    if ctx_tier.dtype != np.int32 or ctx_cfg.dtype != np.int32:
+        raise ValueError("ctx_tier and ctx_cfg must be int32 numpy arrays")
+    if max_ops is None:
+        max_ops = 1 + n_ctx * (n_cfg + len(tiers))
+    ops = (_PolicyOp * max_ops)()
+    n = _i32(0)
+    rc = _lib.kvp_policy_insert(n_ctx, n_cfg, b.ctypes.data, q.ctypes.data, f.ctypes.data, _tiers(tiers), len(tiers),
+                                float(alpha), ctx_tier.ctypes.data, ctx_cfg.ctypes.data, int(incoming), ops, max_ops,
+                                ctypes.byref(n))
+    _check(rc, "kvp_policy_insert")
+    return [(o.ctx, o.cfg, o.tier, o.op) for o in ops[: n.value]]
 
 
 def kvp_copy_bytes(dst: torch.Tensor, src: torch.Tensor, stream=None):

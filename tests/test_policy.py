@@ -1,0 +1,84 @@
+"""The library's host-side policy layer (kvp_utility_table, kvp_policy_insert) against the CPU oracle
+and against the numbers the paper prints.  CPU only: no kernel is involved."""
+import os
+
+import numpy as np
+import pytest
+
+from oracle import policy
+
+GB = 1e9
+
+
+@pytest.fixture(scope="module")
+def kvp():
+    from paper_2512_14946_amd import build
+    if not os.path.exists(build.LIB):
+        build.build_library()
+    import paper_2512_14946_amd as m
+    return m
+
+
+def test_utility_table_matches_oracle_and_paper(kvp):
+    tiers = [(8 * GB, 20 * GB), (80 * GB, 2 * GB), (-1, 0.5 * GB)]
+    q = [1.0, 0.97, 0.8, 0.65]
+    b = [4 * GB, 2 * GB, 1 * GB, 0.2 * GB]
+    got = kvp.kvp_utility_table(q, b, tiers, alpha=1.3, frequency=2.0)
+    want = np.array(policy.utility_table(q, b, tiers, 1.3, 2.0))
+    assert np.array_equal(got, want)
+    # the printed example: quality 0.65 / 0.67 at TTFT 0.05 s (1 GB at 20 GB/s), alpha 1
+    u = kvp.kvp_utility_table([0.65, 0.67], [1 * GB, 1 * GB], [(-1, 20 * GB)], alpha=1.0)
+    assert abs(u[0, 0] - 0.607) <= 0.01 and abs(u[0, 1] - 0.621) <= 0.01 and u[0, 0] < u[0, 1]
+
+
+def test_two_context_figure(kvp):
+    nbytes = [[4 * GB, 2 * GB, 0.2 * GB], [8 * GB, 4 * GB, 0.4 * GB]]
+    quality = [[1.0, 1.0, 1.0], [1.0, 0.5, 0.5]]
+    tiers = [(8 * GB, 20 * GB), (-1.0, 2 * GB)]
+    ctx_tier, ctx_cfg = np.array([0, -1], np.int32), np.array([0, 0], np.int32)
+    ops = kvp.kvp_policy_insert(nbytes, quality, [1.0, 1.0], tiers, 1.0, ctx_tier, ctx_cfg, 1)
+    assert ops == [(1, 0, 0, kvp.KVP_OP_INSERT), (0, 2, 0, kvp.KVP_OP_COMPRESS), (0, 2, 1, kvp.KVP_OP_EVICT)]
+    ttft = sum(nbytes[j][ctx_cfg[j]] / tiers[ctx_tier[j]][1] for j in range(2))
+    assert ttft == pytest.approx(0.5) and all(quality[j][ctx_cfg[j]] == 1.0 for j in range(2))
+
+
+@pytest.mark.parametrize("seed", range(20))
+def test_random_instances_match_oracle(kvp, seed):
+    rng = np.random.default_rng(seed)
+    n_ctx, n_cfg, n_tiers = int(rng.integers(2, 9)), int(rng.integers(1, 5)), int(rng.integers(1, 4))
+    size = rng.uniform(0.5, 8.0, n_ctx) * GB
+    frac = np.sort(rng.uniform(0.05, 1.0, (n_ctx, n_cfg)), axis=1)[:, ::-1]
+    frac[:, 0] = 1.0
+    nbytes = size[:, None] * frac
+    quality = np.clip(1.0 - rng.uniform(0, 0.6, (n_ctx, 1)) * (1 - frac) ** rng.uniform(0.5, 3), 0, 1)
+    if seed % 3 == 0:
+        quality = np.round(quality, 1)                    # many ties
+    freq = rng.integers(1, 5, n_ctx).astype(float)
+    tiers = [(float(rng.uniform(2, 12)) * GB, 20 * GB / 10 ** d) for d in range(n_tiers)]
+    tiers[-1] = (-1.0, tiers[-1][1])
+    alpha = float(rng.choice([0.1, 0.5, 1.0, 3.0]))
+    t_lib, c_lib = np.full(n_ctx, -1, np.int32), np.zeros(n_ctx, np.int32)
+    t_ref, c_ref = [-1] * n_ctx, [0] * n_ctx
+    for i in rng.permutation(n_ctx):
+        got = kvp.kvp_policy_insert(nbytes, quality, freq, tiers, alpha, t_lib, c_lib, int(i))
+        want = policy.insert(nbytes.tolist(), quality.tolist(), freq.tolist(), tiers, alpha, t_ref, c_ref, int(i))
+        assert got == want
+        assert t_lib.tolist() == t_ref and c_lib.tolist() == c_ref
+        for d, (cap, _) in enumerate(tiers):              # every bounded tier fits
+            if cap >= 0:
+                assert sum(nbytes[j, c_lib[j]] for j in range(n_ctx) if t_lib[j] == d) <= cap
+        assert got[0][3] == kvp.KVP_OP_INSERT and all(o[3] != kvp.KVP_OP_INSERT for o in got[1:])
+
+
+def test_errors(kvp):
+    nbytes, quality = [[4 * GB]], [[1.0]]
+    t, c = np.array([-1], np.int32), np.array([0], np.int32)
+    with pytest.raises(kvp.KVPError):                      # a bounded last tier that cannot fit
+        kvp.kvp_policy_insert(nbytes, quality, [1.0], [(1 * GB, 20 * GB)], 1.0, t, c, 0)
+    with pytest.raises(kvp.KVPError):                      # bandwidth must be positive
+        kvp.kvp_utility_table([1.0], [1.0], [(-1, 0.0)], 1.0)
+    t, c = np.array([-1, 0], np.int32), np.array([0, 0], np.int32)
+    with pytest.raises(kvp.KVPError) as e:                 # ops buffer too small
+        kvp.kvp_policy_insert([[4 * GB], [4 * GB]], [[1.0], [1.0]], [1.0, 1.0], [(5 * GB, 20 * GB), (-1, 2 * GB)], 1.0,
+                              t, c, 0, max_ops=1)
+    assert e.value.code == -5
