@@ -246,8 +246,8 @@ def side_measurements(kvp, workloads, torch, dev, K8, V8):
     for name, bits, group in [("int8_g128", 8, 128), ("int2_g32", 2, 32), ("int4_g32", 4, 32)]:
         qp = kvp.alloc_qplane(L, T, H, D, bits, group, dev)
         pg = kvp.alloc_paged(L, T, H, D, bt, nb, 16)
-        tq = _time_loop(torch, lambda: kvp.kvp_quantize(K8, qp), 5)
-        td = _time_loop(torch, lambda: kvp.kvp_dequantize_paged(qp, pg), 5)
+        tq = _time_loop(torch, lambda: kvp.kvp_quantize(K8, qp), 10, warm=2)
+        td = _time_loop(torch, lambda: kvp.kvp_dequantize_paged(qp, pg), 10, warm=2)
         alg = K8.numel() * 2 + qp.nbytes()
         if name == "int4_g32":
             ident = kvp.PagedKV(pg.pool, torch.arange(nb, dtype=torch.int32, device=dev), T)
@@ -260,6 +260,50 @@ def side_measurements(kvp, workloads, torch, dev, K8, V8):
                      "quantize_frac_hbm": round(alg / tq / 1e9 / HBM_PEAK_GBS, 4),
                      "dequantize_frac_hbm": round(alg / td / 1e9 / HBM_PEAK_GBS, 4)}
         del qp, pg
+    # --- single-layer int8 config: 8 MiB planes are cache-resident and launch-bound; a rotating set of
+    #     64 independent copies (512 MiB per plane set) defeats the 256 MB last-level cache ---
+    c1 = workloads.CONFIGS["single_layer_int8"]
+    n_rot = 64
+    K1, _ = workloads.make_kv(n_rot, c1["T"], c1["H"], c1["D"], seed=0, device=dev)   # n_rot independent "layers"
+    bt1, nb1 = workloads.make_block_table(c1["T"], 16, seed=0, device=dev)
+    q1 = [kvp.alloc_qplane(1, c1["T"], c1["H"], c1["D"], 8, 128, dev) for _ in range(n_rot)]
+    p1 = [kvp.alloc_paged(1, c1["T"], c1["H"], c1["D"], bt1, nb1, 16) for _ in range(n_rot)]
+    views = [K1[i:i + 1] for i in range(n_rot)]
+    alg1 = views[0].numel() * 2 + q1[0].nbytes()
+
+    def rot_q():
+        for i in range(n_rot):
+            kvp.kvp_quantize(views[i], q1[i])
+
+    def rot_d():
+        for i in range(n_rot):
+            kvp.kvp_dequantize_paged(q1[i], p1[i])
+    t_same_q = _time_loop(torch, lambda: kvp.kvp_quantize(views[0], q1[0]), 50, warm=5)
+    t_same_d = _time_loop(torch, lambda: kvp.kvp_dequantize_paged(q1[0], p1[0]), 50, warm=5)
+    t_rot_q = _time_loop(torch, rot_q, 3) / n_rot
+    t_rot_d = _time_loop(torch, rot_d, 3) / n_rot
+    ops["single_layer_int8"] = {
+        "workload": f"1x{c1['H']}x{c1['D']}x{c1['T']} plane (8 MiB), int8 g128; 'rotating' = {n_rot} independent copies in turn",
+        "quantize_us_cache_resident": round(t_same_q * 1e6, 1), "dequantize_us_cache_resident": round(t_same_d * 1e6, 1),
+        "quantize_us_rotating": round(t_rot_q * 1e6, 1), "dequantize_us_rotating": round(t_rot_d * 1e6, 1),
+        "quantize_GBs_alg_rotating": round(alg1 / t_rot_q / 1e9, 1), "dequantize_GBs_alg_rotating": round(alg1 / t_rot_d / 1e9, 1),
+        "note": "launch-bound: one call moves 16.3 MB (2 us at peak); times include the per-call launch path"}
+    del K1, q1, p1, views
+    # --- long-context int2 config at its true shape (4 KV heads: 16 KiB pages, outlier channels x16) ---
+    c5 = workloads.CONFIGS["long_context_int2"]
+    K5, _ = workloads.make_kv(c5["L"], c5["T"], c5["H"], c5["D"], seed=0, outlier_scale=c5["outlier_scale"], device=dev)
+    bt5, nb5 = workloads.make_block_table(c5["T"], 16, seed=0, device=dev)
+    q5 = kvp.alloc_qplane(c5["L"], c5["T"], c5["H"], c5["D"], 2, 32, dev)
+    p5 = kvp.alloc_paged(c5["L"], c5["T"], c5["H"], c5["D"], bt5, nb5, 16)
+    t5q = _time_loop(torch, lambda: kvp.kvp_quantize(K5, q5), 5)
+    t5d = _time_loop(torch, lambda: kvp.kvp_dequantize_paged(q5, p5), 5)
+    alg5 = K5.numel() * 2 + q5.nbytes()
+    ops["long_context_int2"] = {"workload": f"{c5['L']}x{c5['H']}x{c5['D']}x{c5['T']} plane (3.5 GiB), int2 g32",
+                                "quantize_ms": round(t5q * 1e3, 3), "dequantize_ms": round(t5d * 1e3, 3),
+                                "quantize_frac_hbm": round(alg5 / t5q / 1e9 / HBM_PEAK_GBS, 4),
+                                "dequantize_frac_hbm": round(alg5 / t5d / 1e9 / HBM_PEAK_GBS, 4),
+                                "compress_decompress_input_GBs": round(K5.numel() * 2 / (t5q + t5d) / 1e9, 1)}
+    del K5, q5, p5
     # --- key-only importance scores (knorm, keydiff) on the resident K plane ---
     sc8 = torch.empty(L, H, T, dtype=torch.float32, device=dev)
     wsk = torch.empty(kvp.kvp_score_keys_workspace_bytes(L, H, T, kvp.KVP_SCORE_KEYDIFF) + 16, dtype=torch.uint8, device=dev)
