@@ -22,6 +22,8 @@
 //   oracle_quantize / oracle_dequantize_paged / oracle_select_topk: pinned by
 //     hand-exact examples, exact rational arithmetic, invariants and brute
 //     force (tests/test_oracle_*.py).
+//   oracle_quantize_asym / oracle_dequantize_paged_asym: pinned the same way (hand-exact
+//     examples, exact rational arithmetic, invariants).
 //   oracle_score_keys (knorm, keydiff): pinned by closed forms (3-4-5 norms, identical / orthogonal /
 //     antipodal keys), scale invariance and a library float64 normalize + matmul.
 //   oracle_score_tokens / oracle_eval_configs: pinned by closed forms,
@@ -123,6 +125,58 @@ void dequantize_row(const uint8_t* codes, const float* scales, int64_t D, int bi
     int v = static_cast<int>((byte >> (bits * (c % per_byte))) & field_mask);
     if (v & sign_bit) v -= (1 << bits);
     const float y = static_cast<float>(v) * scales[c / group];
+    out[c] = f32_to_bf16_rne(y);
+  }
+}
+
+// Asymmetric (min / scale) variant of the row quantizer: every one of the 2^bits levels is used,
+// which matters most at 2 bits (the uniform quantization with zero point that the paper's Related
+// work cites as the uniform method).  Per group:
+//   mn = min x, mx = max x                      (exact)
+//   scale = fl32(fl32(mx - mn) / (2^bits - 1))  (one binary32 subtraction, one division)
+//   q = clamp(rint(fl32(fl32(x - mn) / scale)), 0, 2^bits - 1), 0 when scale == 0   (unsigned fields)
+// and back: y = bf16_rne(fl32(fl32(q * scale) + mn))   (a multiply and an add, not fused).
+void quantize_row_asym(const uint16_t* x, int64_t D, int bits, int group, uint8_t* codes, float* scales, float* mins) {
+  const int levels = (1 << bits) - 1;
+  const int per_byte = 8 / bits;
+  std::vector<int> q(static_cast<size_t>(D));
+  for (int64_t g0 = 0; g0 < D; g0 += group) {
+    float mn = bf16_to_f32(x[g0]), mx = mn;
+    for (int64_t c = 1; c < group; ++c) {
+      const float v = bf16_to_f32(x[g0 + c]);
+      mn = std::min(mn, v);
+      mx = std::max(mx, v);
+    }
+    if (mn == 0.0f) mn = 0.0f;  // -0 and +0 compare equal: store +0 so the bytes are unique
+    const float range = mx - mn;
+    const float scale = range / static_cast<float>(levels);
+    scales[g0 / group] = scale;
+    mins[g0 / group] = mn;
+    for (int64_t c = 0; c < group; ++c) {
+      int v = 0;
+      if (scale != 0.0f) {
+        const float d = bf16_to_f32(x[g0 + c]) - mn;
+        v = static_cast<int>(std::rint(d / scale));
+        v = std::min(levels, std::max(0, v));
+      }
+      q[static_cast<size_t>(g0 + c)] = v;
+    }
+  }
+  for (int64_t m = 0; m < D / per_byte; ++m) {
+    uint32_t byte = 0;
+    for (int i = 0; i < per_byte; ++i) byte |= static_cast<uint32_t>(q[static_cast<size_t>(m * per_byte + i)]) << (bits * i);
+    codes[m] = static_cast<uint8_t>(byte);
+  }
+}
+
+void dequantize_row_asym(const uint8_t* codes, const float* scales, const float* mins, int64_t D, int bits, int group,
+                         uint16_t* out) {
+  const int per_byte = 8 / bits;
+  const uint32_t field_mask = (1u << bits) - 1u;
+  for (int64_t c = 0; c < D; ++c) {
+    const uint32_t v = (codes[c / per_byte] >> (bits * (c % per_byte))) & field_mask;
+    const float prod = static_cast<float>(v) * scales[c / group];
+    const float y = prod + mins[c / group];
     out[c] = f32_to_bf16_rne(y);
   }
 }
@@ -288,6 +342,56 @@ int oracle_dequantize_paged(const uint8_t* codes, const float* scales, int bits,
         const float* s = scales + ((l * Tp + t) * H + h) * ns;
         uint16_t* row = pool + l * pool_stride_l + ((blk * bs + t % bs) * H + h) * D;
         dequantize_row(c, s, D, bits, group, row);
+      }
+    }
+  return 0;
+}
+
+// Asymmetric variants: same layouts as oracle_quantize / oracle_dequantize_paged plus
+// mins[L][Tp][H][D/group]; codes are unsigned fields.  Flat strided source, optional keep list.
+int oracle_quantize_asym(const uint16_t* x, int64_t L, int64_t T, int64_t H, int64_t D, int64_t stride_l,
+                         int64_t stride_t, int64_t stride_h, const int32_t* keep_idx, int64_t k, int bits, int group,
+                         int64_t Tp, uint8_t* codes, float* scales, float* mins) {
+  if (!x || !codes || !scales || !mins || !quant_args_ok(bits, group, D)) return -1;
+  const int64_t n_slots = keep_idx ? k : T;
+  if (n_slots < 0 || n_slots > Tp || L < 0 || T < 0 || H <= 0) return -1;
+  const int64_t cb = D * bits / 8, ns = D / group;
+  const View v{x, stride_l, stride_t, stride_h};
+  for (int64_t l = 0; l < L; ++l)
+    for (int64_t i = 0; i < Tp; ++i)
+      for (int64_t h = 0; h < H; ++h) {
+        uint8_t* c = codes + ((l * Tp + i) * H + h) * cb;
+        float* s = scales + ((l * Tp + i) * H + h) * ns;
+        float* m = mins + ((l * Tp + i) * H + h) * ns;
+        if (i >= n_slots) {
+          std::memset(c, 0, static_cast<size_t>(cb));
+          for (int64_t j = 0; j < ns; ++j) s[j] = m[j] = 0.0f;
+          continue;
+        }
+        int64_t t = i;
+        if (keep_idx) {
+          t = keep_idx[(l * H + h) * k + i];
+          if (t < 0 || t >= T) return -1;
+        }
+        quantize_row_asym(v.row(l, t, h), D, bits, group, c, s, m);
+      }
+  return 0;
+}
+
+int oracle_dequantize_paged_asym(const uint8_t* codes, const float* scales, const float* mins, int bits, int group,
+                                 int64_t L, int64_t T, int64_t Tp, int64_t H, int64_t D, const int32_t* block_table,
+                                 int64_t num_blocks, int64_t bs, uint16_t* pool, int64_t pool_stride_l) {
+  if (!codes || !scales || !mins || !block_table || !pool || !quant_args_ok(bits, group, D) || bs <= 0 || T > Tp)
+    return -1;
+  const int64_t cb = D * bits / 8, ns = D / group;
+  for (int64_t l = 0; l < L; ++l)
+    for (int64_t t = 0; t < T; ++t) {
+      const int64_t blk = block_table[t / bs];
+      if (blk < 0 || blk >= num_blocks) return -1;
+      for (int64_t h = 0; h < H; ++h) {
+        const int64_t r = (l * Tp + t) * H + h;
+        uint16_t* row = pool + l * pool_stride_l + ((blk * bs + t % bs) * H + h) * D;
+        dequantize_row_asym(codes + r * cb, scales + r * ns, mins + r * ns, D, bits, group, row);
       }
     }
   return 0;

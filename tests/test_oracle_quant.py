@@ -35,16 +35,20 @@ def _unpack(codes: np.ndarray, bits: int) -> np.ndarray:
     return fields.reshape(*codes.shape[:-1], codes.shape[-1] * per)
 
 
-def _golden_cases():
+def _golden_cases(asym=False):
     cases = []
     with open(GOLDEN) as f:
         for line in f:
             line = line.strip()
             if not line or line.startswith("#"):
                 continue
-            name, bits, xs, scale_hex, bytes_hex = [p.strip() for p in line.split("|")]
-            cases.append((name, int(bits), [float(v) for v in xs.split()], int(scale_hex, 16),
-                          [int(b, 16) for b in bytes_hex.split()]))
+            parts = [p.strip() for p in line.split("|")]
+            name, bits, xs, scale_hex, bytes_hex = parts[:5]
+            if name.startswith("asym_") != asym:
+                continue
+            case = (name, int(bits), [float(v) for v in xs.split()], int(scale_hex, 16),
+                    [int(b, 16) for b in bytes_hex.split()])
+            cases.append(case + ((int(parts[5], 16),) if asym else ()))
     return cases
 
 
@@ -256,3 +260,72 @@ def test_keep_count():
     assert [oracle.keep_count(r, 8192) for r in (0.25, 0.5, 0.75)] == [2048, 4096, 6144]
     assert oracle.keep_count(0.0, 10) == 1 and oracle.keep_count(1.5, 10) == 10
     assert oracle.keep_count(0.34, 3) == 2          # ceil(1.02)
+
+
+# ---------------------------------------------------------------- asymmetric variant
+
+@pytest.mark.parametrize("name,bits,xs,scale_bits,expect_bytes,min_bits", _golden_cases(asym=True),
+                         ids=lambda c: str(c)[:24])
+def test_asym_hand_worked_examples(name, bits, xs, scale_bits, expect_bytes, min_bits):
+    codes, scales, mins = oracle.quantize_asym(_row(xs), bits, len(xs))
+    assert scales.view(np.uint32).ravel().tolist() == [scale_bits], name
+    assert mins.view(np.uint32).ravel().tolist() == [min_bits], name
+    assert codes.ravel().tolist() == expect_bytes, name
+
+
+def _unpack_unsigned(codes, bits):
+    per = 8 // bits
+    c = codes.astype(np.int32)
+    f = np.stack([(c >> (bits * i)) & ((1 << bits) - 1) for i in range(per)], axis=-1)
+    return f.reshape(*codes.shape[:-1], codes.shape[-1] * per)
+
+
+@pytest.mark.parametrize("bits", [8, 4, 2])
+def test_asym_exact_rational_arithmetic(bits):
+    rng = np.random.default_rng(bits + 50)
+    D, group, levels = 64, 16, (1 << bits) - 1
+    vals = rng.standard_normal((5, D)).astype(np.float32)
+    vals[1] = np.round(vals[1] * 4) / 4
+    vals[2, :group] = 1.5                                  # constant group: scale 0
+    vals[3] *= 1e3
+    vals[4] = np.abs(vals[4]) * 2.0 ** -30
+    x = to_bf16_bits(vals).reshape(1, 5, 1, D)
+    codes, scales, mins = oracle.quantize_asym(x, bits, group)
+    pool = oracle.dequantize_paged_asym(codes, scales, mins, bits, group, 5, np.array([0], np.int32), 1, 16)
+    for t in range(5):
+        xs = [frac_of_f32(v) for v in bits_to_f32(x[0, t, 0])]
+        q = _unpack_unsigned(codes[0, t, 0], bits)
+        for g in range(D // group):
+            grp = xs[g * group:(g + 1) * group]
+            mn, mx = min(grp), max(grp)
+            scale = fl32(fl32(mx - mn) / levels)
+            assert Fraction(float(scales[0, t, 0, g])) == scale and Fraction(float(mins[0, t, 0, g])) == mn
+            for c, v in enumerate(grp):
+                want = 0 if scale == 0 else max(0, min(levels, rint_even(fl32(fl32(v - mn) / scale))))
+                assert q[g * group + c] == want
+                back = flbf16(fl32(fl32(Fraction(int(want)) * scale) + mn))
+                assert Fraction(float(bits_to_f32(pool[0, 0, t, 0, g * group + c:g * group + c + 1])[0])) == back
+
+
+@pytest.mark.parametrize("bits,group", [(8, 128), (4, 32), (2, 32), (2, 128)])
+def test_asym_invariants_and_gain_over_symmetric(bits, group):
+    _, V = workloads.make_kv(2, 64, 2, 128, seed=9)       # V: no outlier channels (a one-sided outlier can
+    x = torch_bits(V)                                     # make the 4-level asymmetric grid coarser near 0)
+    xf = bits_to_f32(x).astype(np.float64)
+    codes, scales, mins = oracle.quantize_asym(x, bits, group)
+    levels = (1 << bits) - 1
+    q = _unpack_unsigned(codes, bits).astype(np.float64)
+    s = np.repeat(scales.astype(np.float64), group, -1)
+    m = np.repeat(mins.astype(np.float64), group, -1)
+    assert q.min() >= 0 and q.max() <= levels
+    # |q*scale + min - x| <= scale/2 plus the binary32 roundings of the difference and the quotient
+    assert np.all(np.abs(q * s + m - xf) <= s * (0.5 + levels * 2.0 ** -23) + np.abs(xf - m) * 2.0 ** -23)
+    # the group minimum maps to code 0 and the maximum to the top level
+    qg = q.reshape(*q.shape[:-1], -1, group)
+    assert np.all(qg.min(-1) == 0) and np.all(qg.max(-1)[scales > 0] == levels)
+    # using every level, the reconstruction error is smaller than the symmetric quantizer's
+    bt = np.arange(4, dtype=np.int32)
+    ya = bits_to_f32(oracle.dequantize_paged_asym(codes, scales, mins, bits, group, 64, bt, 4, 16).reshape(2, 64, 2, 128))
+    cs, ss = oracle.quantize(x, bits, group)
+    ys = bits_to_f32(oracle.dequantize_paged(cs, ss, bits, group, 64, bt, 4, 16).reshape(2, 64, 2, 128))
+    assert np.square(ya - xf).sum() < np.square(ys - xf).sum()
