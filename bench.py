@@ -243,8 +243,9 @@ def side_measurements(kvp, workloads, torch, dev, K8, V8):
     # --- int8 g128 and int2 g32 codecs on the resident 8B-shaped planes (beyond the last-level cache) ---
     L, T, H, D = K8.shape
     bt, nb = workloads.make_block_table(T, 16, seed=0, device=dev)
-    for name, bits, group in [("int8_g128", 8, 128), ("int2_g32", 2, 32), ("int4_g32", 4, 32)]:
-        qp = kvp.alloc_qplane(L, T, H, D, bits, group, dev)
+    for name, bits, group in [("int8_g128", 8, 128), ("int2_g32", 2, 32), ("int4_g32", 4, 32),
+                              ("asymmetric_int4_g64", 4, 64), ("asymmetric_int2_g32", 2, 32)]:
+        qp = kvp.alloc_qplane(L, T, H, D, bits, group, dev, asymmetric=name.startswith("asymmetric"))
         pg = kvp.alloc_paged(L, T, H, D, bt, nb, 16)
         tq = _time_loop(torch, lambda: kvp.kvp_quantize(K8, qp), 10, warm=2)
         td = _time_loop(torch, lambda: kvp.kvp_dequantize_paged(qp, pg), 10, warm=2)

@@ -72,6 +72,7 @@ typedef struct {
 typedef struct {
   uint8_t* codes; /* device [L][Tp][H][D*bits/8] */
   float* scales;  /* device [L][Tp][H][D/group] */
+  float* mins;    /* NULL: symmetric codec.  Else device [L][Tp][H][D/group]: asymmetric codec (see kvp_quantize) */
   int32_t bits, group;
   int64_t L, T, Tp, H, D;
 } kvp_qplane;
@@ -96,7 +97,11 @@ typedef struct {
  * `keep_idx` (device int32 [L][H][k], ascending, values in [0, T)) slot i of
  * head h takes source token keep_idx[l][h][i] and dst->T must equal k;
  * otherwise slot i is token i, k is ignored and dst->T must equal the source
- * T.  Writes dst->codes and dst->scales in full, padding slots included. */
+ * T.  Writes dst->codes and dst->scales in full, padding slots included.
+ * With dst->mins != NULL the asymmetric variant is used instead (uniform quantization with a
+ * zero point, all 2^bits levels): per group mn = min x, scale = fl32(fl32(max x - mn) / (2^bits - 1)),
+ * code = clamp(rint(fl32(fl32(x - mn) / scale)), 0, 2^bits - 1) as an UNSIGNED field, mins = mn;
+ * kvp_dequantize_paged then returns bf16_rne(fl32(fl32(code * scale) + mn)). */
 int32_t kvp_quantize(const kvp_view* src, const kvp_paged* src_paged, const int32_t* keep_idx, int64_t k,
                      const kvp_qplane* dst, void* stream);
 

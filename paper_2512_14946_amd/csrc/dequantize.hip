@@ -22,6 +22,7 @@ constexpr int kUnroll = 8;                             // a 16-token x 8-head pa
 struct DequantArgs {
   const uint8_t* codes;
   const float* scales;
+  const float* mins;   // asymmetric codec only
   uint16_t* pool;
   const int32_t* block_table;
   int64_t pool_stride_l;   // elements
@@ -44,18 +45,18 @@ __device__ __forceinline__ uint2 load_codes<2>(const uint8_t* row_codes, int lan
   return make_uint2(load_stream2(row_codes + lane_in_row * 2), 0);
 }
 
-// signed field i (of 8) of a lane's packed codes
-template <int BITS>
+// field i (of 8) of a lane's packed codes: signed (symmetric codec) or unsigned (asymmetric codec)
+template <int BITS, bool ASYM>
 __device__ __forceinline__ int field(const uint2 c, int i) {
-  if constexpr (BITS == 8) {
-    const uint32_t w = i < 4 ? c.x : c.y;
-    return __builtin_amdgcn_sbfe(static_cast<int>(w), 8 * (i & 3), 8);
-  } else {
-    return __builtin_amdgcn_sbfe(static_cast<int>(c.x), BITS * i, BITS);
-  }
+  const uint32_t w = (BITS == 8 && i >= 4) ? c.y : c.x;
+  const int off = BITS == 8 ? 8 * (i & 3) : BITS * i;
+  if constexpr (ASYM)
+    return static_cast<int>(__builtin_amdgcn_ubfe(w, off, BITS));
+  else
+    return __builtin_amdgcn_sbfe(static_cast<int>(w), off, BITS);
 }
 
-template <int BITS, int GROUP>
+template <int BITS, int GROUP, bool ASYM>
 __global__ __launch_bounds__(kThreads) void dequantize_paged_kernel(const DequantArgs a) {
   constexpr int CB = kHeadDim * BITS / 8;
   constexpr int NS = kHeadDim / GROUP;
@@ -72,17 +73,20 @@ __global__ __launch_bounds__(kThreads) void dequantize_paged_kernel(const Dequan
   const int64_t src_row0 = (static_cast<int64_t>(l) * a.Tp + t0) * a.H;
   const uint8_t* codes = a.codes + src_row0 * CB;
   const float* scales = a.scales + src_row0 * NS;
+  const float* mins = ASYM ? a.mins + src_row0 * NS : nullptr;
   uint16_t* dst = a.pool + static_cast<int64_t>(l) * a.pool_stride_l + blk * a.bs * a.H * kHeadDim;
 
   for (uint32_t r0 = row_in_step; r0 < rows; r0 += kRowsPerStep * kUnroll) {
     uint2 c[kUnroll];
-    float s[kUnroll];
+    float s[kUnroll], m[kUnroll];
 #pragma unroll
     for (int u = 0; u < kUnroll; ++u) {
       const uint32_t r = r0 + u * kRowsPerStep;
       c[u] = make_uint2(0, 0);
       s[u] = 0.0f;
+      m[u] = 0.0f;
       if (r < rows) {
+        if constexpr (ASYM) m[u] = __builtin_nontemporal_load(mins + static_cast<int64_t>(r) * NS + lane_in_row / LANES_PER_GROUP);
         c[u] = load_codes<BITS>(codes + static_cast<int64_t>(r) * CB, lane_in_row);
         s[u] = __builtin_nontemporal_load(scales + static_cast<int64_t>(r) * NS + lane_in_row / LANES_PER_GROUP);
       }
@@ -94,8 +98,12 @@ __global__ __launch_bounds__(kThreads) void dequantize_paged_kernel(const Dequan
       uint32_t w[4];
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        const float lo = static_cast<float>(field<BITS>(c[u], 2 * i)) * s[u];
-        const float hi = static_cast<float>(field<BITS>(c[u], 2 * i + 1)) * s[u];
+        float lo = static_cast<float>(field<BITS, ASYM>(c[u], 2 * i)) * s[u];
+        float hi = static_cast<float>(field<BITS, ASYM>(c[u], 2 * i + 1)) * s[u];
+        if constexpr (ASYM) {   // a separate binary32 add (contraction is off for this library)
+          lo = lo + m[u];
+          hi = hi + m[u];
+        }
         w[i] = pack_bf16x2(lo, hi);
       }
       store_stream16(dst + static_cast<int64_t>(r) * kHeadDim + lane_in_row * 8, make_uint4(w[0], w[1], w[2], w[3]));
@@ -103,13 +111,21 @@ __global__ __launch_bounds__(kThreads) void dequantize_paged_kernel(const Dequan
   }
 }
 
+template <int BITS, bool ASYM>
+void launch_group2(int group, dim3 grid, hipStream_t st, const DequantArgs& a) {
+  switch (group) {
+    case 32: dequantize_paged_kernel<BITS, 32, ASYM><<<grid, kThreads, 0, st>>>(a); break;
+    case 64: dequantize_paged_kernel<BITS, 64, ASYM><<<grid, kThreads, 0, st>>>(a); break;
+    default: dequantize_paged_kernel<BITS, 128, ASYM><<<grid, kThreads, 0, st>>>(a); break;
+  }
+}
+
 template <int BITS>
 void launch_group(int group, dim3 grid, hipStream_t st, const DequantArgs& a) {
-  switch (group) {
-    case 32: dequantize_paged_kernel<BITS, 32><<<grid, kThreads, 0, st>>>(a); break;
-    case 64: dequantize_paged_kernel<BITS, 64><<<grid, kThreads, 0, st>>>(a); break;
-    default: dequantize_paged_kernel<BITS, 128><<<grid, kThreads, 0, st>>>(a); break;
-  }
+  if (a.mins)
+    launch_group2<BITS, true>(group, grid, st, a);
+  else
+    launch_group2<BITS, false>(group, grid, st, a);
 }
 
 __global__ __launch_bounds__(256) void copy_kernel(uint4* __restrict__ dst, const uint4* __restrict__ src, size_t n16) {
@@ -133,6 +149,7 @@ extern "C" int32_t kvp_dequantize_paged(const kvp_qplane* src, const kvp_paged* 
   DequantArgs a{};
   a.codes = src->codes;
   a.scales = src->scales;
+  a.mins = src->mins;
   a.pool = static_cast<uint16_t*>(dst->pool);
   a.block_table = dst->block_table;
   a.pool_stride_l = dst->stride_l;

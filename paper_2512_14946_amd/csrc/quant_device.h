@@ -93,6 +93,74 @@ struct GroupQuantizer {
   }
 };
 
+// Asymmetric codec: codes 0 .. LEVELS of d = fl32(x - mn) on the scale fl32(fl32(mx - mn) / LEVELS).
+// Same reciprocal fast path and exact fallbacks as GroupQuantizer, applied to d.
+template <int LEVELS>
+struct AsymQuantizer {
+  float scale, inv, mn;
+  bool unsafe;
+  __device__ __forceinline__ AsymQuantizer(float gmin, float gmax) {
+    mn = gmin + 0.0f;                                   // -0 -> +0, everything else unchanged
+    const float range = gmax - mn;
+    // range / LEVELS, correctly rounded without a division: product with the rounded reciprocal,
+    // exact remainder, one correction (checked against IEEE division for all 2^23 significands and
+    // LEVELS = 3, 15, 255).  Outside the exponent range where no step under- or overflows: divide.
+    constexpr float kLevels = static_cast<float>(LEVELS);
+    constexpr float kInvLevels = 1.0f / kLevels;
+    const float q0 = range * kInvLevels;
+    scale = fmaf(fmaf(-kLevels, q0, range), kInvLevels, q0);
+    unsafe = !(q0 >= 0x1p-100f && q0 <= 0x1p100f) && range != 0.0f;
+    if (__builtin_amdgcn_ballot_w64(unsafe)) {
+      if (unsafe) scale = range / kLevels;
+    }
+    unsafe = unsafe && scale != 0.0f;
+    inv = (scale == 0.0f) ? 0.0f : __builtin_amdgcn_rcpf(scale);
+  }
+  static constexpr float kTieMargin = static_cast<float>(LEVELS + 1) * 0x1p-20f;
+
+  __device__ __forceinline__ float code(float x) const {
+    const float d0 = x - mn;
+    const float y0 = d0 * inv;
+    float q = rintf(y0);
+    const float d = y0 - q;  // exact
+    const bool risky = fabsf(d) > 0.5f - kTieMargin;
+    if (__builtin_amdgcn_ballot_w64(risky)) {
+      if (risky) {
+        const float h = q + copysignf(0.5f, d);
+        const float e = fmaf(-h, scale, d0);
+        const bool divide = e != 0.0f;
+        if (!divide) q = rintf(h);
+        if (__builtin_amdgcn_ballot_w64(divide)) {
+          if (divide) q = rintf(d0 / scale);
+        }
+      }
+    }
+    return q;
+  }
+  __device__ __forceinline__ void codes8(const float x[8], float q[8]) const {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) q[i] = code(x[i]);
+    if (__builtin_amdgcn_ballot_w64(unsafe)) {
+      if (unsafe) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) q[i] = fminf(static_cast<float>(LEVELS), fmaxf(0.0f, rintf((x[i] - mn) / scale)));
+      }
+    }
+  }
+};
+
+template <int CTRL>
+__device__ __forceinline__ float dpp_peer(float v) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(v), __float_as_int(v), CTRL, 0xf, 0xf, false));
+}
+// min and max over the `lanes` adjacent lanes (4, 8 or 16, aligned) of a quantization group
+__device__ __forceinline__ void group_min_max(float& lo, float& hi, int lanes) {
+  lo = fminf(lo, dpp_peer<0xB1>(lo)); hi = fmaxf(hi, dpp_peer<0xB1>(hi));
+  lo = fminf(lo, dpp_peer<0x4E>(lo)); hi = fmaxf(hi, dpp_peer<0x4E>(hi));
+  if (lanes >= 8) { lo = fminf(lo, dpp_peer<0x141>(lo)); hi = fmaxf(hi, dpp_peer<0x141>(hi)); }
+  if (lanes >= 16) { lo = fminf(lo, dpp_peer<0x140>(lo)); hi = fmaxf(hi, dpp_peer<0x140>(hi)); }
+}
+
 // int2: codes are -1, 0, +1 and scale = amax.  x / amax is a ratio of two 8-bit significands, so it
 // is either exactly 1/2 (code 0: ties go to even) or at least 1/510 away from it.  Multiplying by a
 // reciprocal shrunk by 2^-20 keeps exact ties below 1/2 and cannot move any other quotient across
@@ -150,6 +218,22 @@ __device__ __forceinline__ uint32_t pack_int2x8(const float q[8]) {
 #pragma unroll
   for (int i = 6; i >= 0; --i) s = fmaf(s, 4.0f, q[i]);
   return static_cast<uint32_t>(s + 43690.0f) ^ 0xAAAAu;  // 0xAAAA
+}
+
+// Unsigned fields (asymmetric codec): plain exact weighted sums.
+__device__ __forceinline__ uint32_t pack_uint4x8(const float q[8]) {
+  const float lo = fmaf(q[3], 4096.0f, fmaf(q[2], 256.0f, fmaf(q[1], 16.0f, q[0])));
+  const float hi = fmaf(q[7], 4096.0f, fmaf(q[6], 256.0f, fmaf(q[5], 16.0f, q[4])));
+  return static_cast<uint32_t>(lo) | (static_cast<uint32_t>(hi) << 16);
+}
+__device__ __forceinline__ uint32_t pack_uint8x4(const float q[4]) {
+  return static_cast<uint32_t>(fmaf(q[1], 256.0f, q[0])) | (static_cast<uint32_t>(fmaf(q[3], 256.0f, q[2])) << 16);
+}
+__device__ __forceinline__ uint32_t pack_uint2x8(const float q[8]) {
+  float s = q[7];
+#pragma unroll
+  for (int i = 6; i >= 0; --i) s = fmaf(s, 4.0f, q[i]);
+  return static_cast<uint32_t>(s);
 }
 
 }  // namespace kvp

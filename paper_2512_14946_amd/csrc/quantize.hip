@@ -38,6 +38,7 @@ struct QuantArgs {
   FastDiv div_h, div_bs;
   uint8_t* codes;
   float* scales;
+  float* mins;   // asymmetric codec only
 };
 
 template <int BITS>
@@ -61,31 +62,54 @@ __device__ __forceinline__ void store_codes<2>(uint8_t* row_codes, int lane_in_r
   store_stream2(row_codes + lane_in_row * 2, p.w);
 }
 
-template <int BITS, int GROUP>
-__device__ __forceinline__ void quantize_lane(const uint4 raw, Packed<BITS>& out, float& scale_out) {
+template <int BITS, int GROUP, bool ASYM>
+__device__ __forceinline__ void quantize_lane(const uint4 raw, Packed<BITS>& out, float& scale_out, float& min_out) {
   float x[8], q[8];
   unpack_bf16x8(raw, x);
-  const float amax = group_max(abs_max8(x), GROUP / 8);
-  if constexpr (BITS == 2) {
-    const TernaryQuantizer tq(amax);
-    scale_out = amax;  // qmax = 1
-    tq.codes8(x, q);
-    out.w = pack_int2x8(q);
-  } else if constexpr (BITS == 4) {
-    const GroupQuantizer<7> gq(amax);
-    scale_out = gq.scale;
-    gq.codes8(x, q);
-    out.w = pack_int4x8(q);
+  if constexpr (ASYM) {
+    float lo = x[0], hi = x[0];
+#pragma unroll
+    for (int i = 1; i < 8; ++i) {
+      lo = fminf(lo, x[i]);
+      hi = fmaxf(hi, x[i]);
+    }
+    group_min_max(lo, hi, GROUP / 8);
+    const AsymQuantizer<(1 << BITS) - 1> aq(lo, hi);
+    scale_out = aq.scale;
+    min_out = aq.mn;
+    aq.codes8(x, q);
+    if constexpr (BITS == 2) {
+      out.w = pack_uint2x8(q);
+    } else if constexpr (BITS == 4) {
+      out.w = pack_uint4x8(q);
+    } else {
+      out.lo = pack_uint8x4(q);
+      out.hi = pack_uint8x4(q + 4);
+    }
   } else {
-    const GroupQuantizer<127> gq(amax);
-    scale_out = gq.scale;
-    gq.codes8(x, q);
-    out.lo = pack_int8x4(q);
-    out.hi = pack_int8x4(q + 4);
+    min_out = 0.0f;
+    const float amax = group_max(abs_max8(x), GROUP / 8);
+    if constexpr (BITS == 2) {
+      const TernaryQuantizer tq(amax);
+      scale_out = amax;  // qmax = 1
+      tq.codes8(x, q);
+      out.w = pack_int2x8(q);
+    } else if constexpr (BITS == 4) {
+      const GroupQuantizer<7> gq(amax);
+      scale_out = gq.scale;
+      gq.codes8(x, q);
+      out.w = pack_int4x8(q);
+    } else {
+      const GroupQuantizer<127> gq(amax);
+      scale_out = gq.scale;
+      gq.codes8(x, q);
+      out.lo = pack_int8x4(q);
+      out.hi = pack_int8x4(q + 4);
+    }
   }
 }
 
-template <int BITS, int GROUP, int MODE>
+template <int BITS, int GROUP, int MODE, bool ASYM>
 __global__ __launch_bounds__(kThreads) void quantize_kernel(const QuantArgs a) {
   constexpr int CB = kHeadDim * BITS / 8;      // code bytes per row
   constexpr int NS = kHeadDim / GROUP;         // scales per row
@@ -141,30 +165,40 @@ __global__ __launch_bounds__(kThreads) void quantize_kernel(const QuantArgs a) {
     const uint32_t rloc = row_in_step + s * kRowsPerStep;
     if (block_row0 + rloc >= a.rows_per_layer) continue;
     Packed<BITS> p;
-    float scale;
-    quantize_lane<BITS, GROUP>(raw[s], p, scale);  // zero rows (padding slots) give zero codes and scales
+    float scale, gmin;
+    quantize_lane<BITS, GROUP, ASYM>(raw[s], p, scale, gmin);  // zero rows (padding slots) give zero codes and scales
     store_codes<BITS>(codes_blk + rloc * CB, lane_in_row, p);
-    if ((lane_in_row % LANES_PER_GROUP) == 0)
+    if ((lane_in_row % LANES_PER_GROUP) == 0) {
       store_stream_f32(scales_blk + rloc * NS + lane_in_row / LANES_PER_GROUP, scale);
+      if constexpr (ASYM) store_stream_f32(a.mins + out_row0 * NS + rloc * NS + lane_in_row / LANES_PER_GROUP, gmin);
+    }
   }
 }
 
-template <int BITS, int GROUP>
+template <int BITS, int GROUP, bool ASYM>
 void launch_mode(int mode, dim3 grid, hipStream_t st, const QuantArgs& a) {
   switch (mode) {
-    case kLinear: quantize_kernel<BITS, GROUP, kLinear><<<grid, kThreads, 0, st>>>(a); break;
-    case kStrided: quantize_kernel<BITS, GROUP, kStrided><<<grid, kThreads, 0, st>>>(a); break;
-    default: quantize_kernel<BITS, GROUP, kPaged><<<grid, kThreads, 0, st>>>(a); break;
+    case kLinear: quantize_kernel<BITS, GROUP, kLinear, ASYM><<<grid, kThreads, 0, st>>>(a); break;
+    case kStrided: quantize_kernel<BITS, GROUP, kStrided, ASYM><<<grid, kThreads, 0, st>>>(a); break;
+    default: quantize_kernel<BITS, GROUP, kPaged, ASYM><<<grid, kThreads, 0, st>>>(a); break;
+  }
+}
+
+template <int BITS, bool ASYM>
+void launch_group2(int group, int mode, dim3 grid, hipStream_t st, const QuantArgs& a) {
+  switch (group) {
+    case 32: launch_mode<BITS, 32, ASYM>(mode, grid, st, a); break;
+    case 64: launch_mode<BITS, 64, ASYM>(mode, grid, st, a); break;
+    default: launch_mode<BITS, 128, ASYM>(mode, grid, st, a); break;
   }
 }
 
 template <int BITS>
 void launch_group(int group, int mode, dim3 grid, hipStream_t st, const QuantArgs& a) {
-  switch (group) {
-    case 32: launch_mode<BITS, 32>(mode, grid, st, a); break;
-    case 64: launch_mode<BITS, 64>(mode, grid, st, a); break;
-    default: launch_mode<BITS, 128>(mode, grid, st, a); break;
-  }
+  if (a.mins)
+    launch_group2<BITS, true>(group, mode, grid, st, a);
+  else
+    launch_group2<BITS, false>(group, mode, grid, st, a);
 }
 
 }  // namespace
@@ -217,6 +251,7 @@ extern "C" int32_t kvp_quantize(const kvp_view* src, const kvp_paged* src_paged,
   a.div_h = FastDiv(a.H);
   a.codes = dst->codes;
   a.scales = dst->scales;
+  a.mins = dst->mins;
   const int rows_per_block = kRowsPerStep * steps_for(dst->bits);
   const dim3 grid(static_cast<unsigned>(ceil_div(a.rows_per_layer, rows_per_block)), static_cast<unsigned>(L));
   const hipStream_t st = as_stream(stream);

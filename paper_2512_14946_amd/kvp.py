@@ -35,7 +35,7 @@ class _Paged(ctypes.Structure):
 
 
 class _QPlane(ctypes.Structure):
-    _fields_ = [("codes", _vp), ("scales", _vp), ("bits", _i32), ("group", _i32),
+    _fields_ = [("codes", _vp), ("scales", _vp), ("mins", _vp), ("bits", _i32), ("group", _i32),
                 ("L", _i64), ("T", _i64), ("Tp", _i64), ("H", _i64), ("D", _i64)]
 
 
@@ -111,13 +111,14 @@ class QPlane:
     bits: int
     group: int
     T: int
+    mins: torch.Tensor | None = None   # set: asymmetric codec (unsigned codes, per-group minimum)
 
     @property
     def Tp(self) -> int:
         return self.codes.shape[1]
 
     def nbytes(self) -> int:
-        return self.codes.numel() + 4 * self.scales.numel()
+        return self.codes.numel() + 4 * self.scales.numel() + (4 * self.mins.numel() if self.mins is not None else 0)
 
 
 @dataclass
@@ -128,11 +129,13 @@ class PagedKV:
     T: int
 
 
-def alloc_qplane(L: int, T: int, H: int, D: int, bits: int, group: int, device, page: int = 16) -> QPlane:
+def alloc_qplane(L: int, T: int, H: int, D: int, bits: int, group: int, device, page: int = 16,
+                 asymmetric: bool = False) -> QPlane:
     Tp = (T + page - 1) // page * page
     codes = torch.empty(L, Tp, H, D * bits // 8, dtype=torch.uint8, device=device)
     scales = torch.empty(L, Tp, H, D // group, dtype=torch.float32, device=device)
-    return QPlane(codes, scales, bits, group, T)
+    mins = torch.empty(L, Tp, H, D // group, dtype=torch.float32, device=device) if asymmetric else None
+    return QPlane(codes, scales, bits, group, T, mins)
 
 
 def alloc_paged(L: int, T: int, H: int, D: int, block_table: torch.Tensor, num_blocks: int, bs: int = 16,
@@ -191,7 +194,12 @@ def _qplane(q: QPlane) -> _QPlane:
     D = cb * 8 // q.bits
     if tuple(q.scales.shape) != (L, Tp, H, D // q.group):
         raise ValueError("scales shape does not match codes")
-    return _QPlane(q.codes.data_ptr(), q.scales.data_ptr(), q.bits, q.group, L, q.T, Tp, H, D)
+    mins = None
+    if q.mins is not None:
+        if q.mins.dtype != torch.float32 or not q.mins.is_contiguous() or tuple(q.mins.shape) != tuple(q.scales.shape):
+            raise ValueError("mins must be contiguous float32 with the shape of scales")
+        mins = q.mins.data_ptr()
+    return _QPlane(q.codes.data_ptr(), q.scales.data_ptr(), mins, q.bits, q.group, L, q.T, Tp, H, D)
 
 
 def _check(rc: int, what: str):
@@ -229,11 +237,11 @@ def kvp_quantize(src, dst: QPlane, keep_idx: torch.Tensor | None = None, stream=
     kp = keep_idx.data_ptr() if keep_idx is not None else None
     qp = _qplane(dst)
     if isinstance(src, PagedKV):
-        _need_cuda(src.pool, src.block_table, dst.codes, dst.scales, keep_idx)
+        _need_cuda(src.pool, src.block_table, dst.codes, dst.scales, dst.mins, keep_idx)
         pg = _paged(src)
         rc = _lib.kvp_quantize(None, ctypes.byref(pg), kp, k, ctypes.byref(qp), _stream(stream))
     else:
-        _need_cuda(src, dst.codes, dst.scales, keep_idx)
+        _need_cuda(src, dst.codes, dst.scales, dst.mins, keep_idx)
         vw = _view(src)
         rc = _lib.kvp_quantize(ctypes.byref(vw), None, kp, k, ctypes.byref(qp), _stream(stream))
     _check(rc, "kvp_quantize")
@@ -241,7 +249,7 @@ def kvp_quantize(src, dst: QPlane, keep_idx: torch.Tensor | None = None, stream=
 
 
 def kvp_dequantize_paged(src: QPlane, dst: PagedKV, stream=None) -> PagedKV:
-    _need_cuda(src.codes, src.scales, dst.pool, dst.block_table)
+    _need_cuda(src.codes, src.scales, src.mins, dst.pool, dst.block_table)
     qp, pg = _qplane(src), _paged(dst)
     _check(_lib.kvp_dequantize_paged(ctypes.byref(qp), ctypes.byref(pg), _stream(stream)), "kvp_dequantize_paged")
     return dst

@@ -65,6 +65,32 @@ def test_quantize_dequantize_full_plane_sampled_rows(name):
     assert bool(torch.isfinite(qp.scales).all()) and bool((qp.scales >= 0).all())
 
 
+def test_asymmetric_full_plane_sampled_rows():
+    kvp = _kvp()
+    c = workloads.CONFIGS["llama3_8b_int4_paged"]
+    L, T, H, D, bits, group, bs = c["L"], c["T"], c["H"], c["D"], c["bits"], c["group"], c["bs"]
+    _say("full plane asymmetric", (L, T, H, D), bits, group)
+    _, V = workloads.make_kv(L, T, H, D, seed=0, outlier_scale=c["outlier_scale"], device=DEV)
+    qp = kvp.alloc_qplane(L, T, H, D, bits, group, DEV, page=bs, asymmetric=True)
+    kvp.kvp_quantize(V, qp)
+    bt, nb = workloads.make_block_table(T, bs, seed=0, device=DEV)
+    pg = kvp.alloc_paged(L, T, H, D, bt, nb, bs)
+    kvp.kvp_dequantize_paged(qp, pg)
+    torch.cuda.synchronize()
+    ls, ts, hs = _sample_rows(L, T, H, 4096, seed=3)
+    li, ti, hi = (torch.from_numpy(x).to(DEV) for x in (ls, ts, hs))
+    rows = torch_bits(V[li, ti, hi])
+    oc, os_, om = oracle.quantize_asym(rows.reshape(1, -1, 1, D), bits, group)
+    assert np.array_equal(qp.codes[li, ti, hi].cpu().numpy(), oc[0, :, 0])
+    assert np.array_equal(qp.scales[li, ti, hi].cpu().numpy().view(np.uint32), os_[0, :, 0].view(np.uint32))
+    assert np.array_equal(qp.mins[li, ti, hi].cpu().numpy().view(np.uint32), om[0, :, 0].view(np.uint32))
+    n = rows.shape[0]
+    ident = np.arange((n + bs - 1) // bs, dtype=np.int32)
+    od = oracle.dequantize_paged_asym(oc, os_, om, bits, group, n, ident, len(ident), bs).reshape(-1, D)[:n]
+    blocks = bt.long()[ti // bs]
+    assert np.array_equal(torch_bits(pg.pool[li, blocks, ti % bs, hi]), od)
+
+
 def test_drop_then_quantize_70b_shape_sampled():
     kvp = _kvp()
     c = workloads.CONFIGS["llama3_70b_drop_int4"]

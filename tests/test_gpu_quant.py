@@ -165,3 +165,122 @@ def test_scale_exact_for_every_bf16_amax(bits):
     oc, os_ = oracle.quantize(xb, bits, 32, Tp=qp.Tp)
     assert np.array_equal(qp.scales.cpu().numpy().view(np.uint32), os_.view(np.uint32))
     assert np.array_equal(qp.codes.cpu().numpy(), oc)
+
+
+def _asym_special_rows(D=128):
+    """Rows whose (x - min)/scale lands on exact .5 ties, plus degenerate ranges."""
+    rng = np.random.default_rng(17)
+    rows = []
+    for levels in (3, 15, 255):
+        # halves on [-a, levels - a]: scale is exactly 1 when both ends are present in every group
+        r = rng.integers(0, 2 * levels + 1, D) / 2.0 - 4.0
+        r[::32] = -4.0
+        r[1::32] = levels - 4.0
+        rows.append(r)
+        # the same grid scaled by 3/8 (scale = 0.375, ties stay exact)
+        rows.append(r * 0.375)
+    rows.append(np.full(D, 1.5))                                           # constant group: range 0
+    rows.append(np.where(np.arange(D) % 2 == 0, 0.0, -0.0))                # +0 / -0 only
+    rows.append(np.abs(rng.standard_normal(D)) + 100.0)                    # far from zero: x - min is exact, range small
+    rows.append(-np.abs(rng.standard_normal(D)) * 2.0 ** 40)               # all negative, large
+    r = rng.standard_normal(D) * 2.0 ** -8
+    r[7] = 900.0                                                           # one-sided outlier
+    rows.append(r)
+    return np.stack(rows).astype(np.float32)
+
+
+@pytest.mark.parametrize("bits,group", ALL_CODECS)
+def test_asymmetric_quantize_dequantize_bit_exact(bits, group):
+    kvp = _kvp()
+    L, T, H, D, bs = 3, 203, 8, 128, 16
+    _say("asym quant/dequant", bits, group, (L, T, H, D))
+    _, V = workloads.make_kv(L, T, H, D, seed=bits * 10 + group + 1)
+    xb = torch_bits(V).copy()
+    sp = torch_bits(torch.from_numpy(np.concatenate([_special_rows(D), _asym_special_rows(D)])).to(torch.bfloat16))
+    xb[0, :sp.shape[0], 0] = sp
+    xb[2, -sp.shape[0]:, 7] = sp
+    x = bits_to_torch(xb, DEV)
+    qp = kvp.alloc_qplane(L, T, H, D, bits, group, DEV, asymmetric=True)
+    qp.codes.fill_(0xEE)
+    qp.scales.fill_(float("nan"))
+    qp.mins.fill_(float("nan"))
+    kvp.kvp_quantize(x, qp)
+    torch.cuda.synchronize()
+    ocodes, oscales, omins = oracle.quantize_asym(xb, bits, group, Tp=qp.Tp)
+    assert np.array_equal(qp.scales.cpu().numpy().view(np.uint32), oscales.view(np.uint32))
+    assert np.array_equal(qp.mins.cpu().numpy().view(np.uint32), omins.view(np.uint32))
+    assert np.array_equal(qp.codes.cpu().numpy(), ocodes)
+
+    bt, nb = workloads.make_block_table(T, bs, seed=4, spare=3, device=DEV)
+    pg = kvp.alloc_paged(L, T, H, D, bt, nb, bs, fill_nan=True)
+    kvp.kvp_dequantize_paged(qp, pg)
+    torch.cuda.synchronize()
+    opool = oracle.dequantize_paged_asym(ocodes, oscales, omins, bits, group, T, bt.cpu().numpy(), nb, bs,
+                                         pool=torch_bits(torch.full((L, nb, bs, H, D), float("nan"),
+                                                                    dtype=torch.bfloat16)).copy())
+    assert np.array_equal(torch_bits(pg.pool), opool)
+
+
+@pytest.mark.parametrize("bits,group", [(4, 64), (2, 32)])
+def test_asymmetric_gather_and_paged_sources(bits, group):
+    kvp = _kvp()
+    L, T, H, D, bs = 2, 150, 4, 128, 16
+    _say("asym sources", bits, group)
+    _, V = workloads.make_kv(L, T, H + 2, D, seed=12)
+    xb_full = torch_bits(V)
+    xv = V.to(DEV)[:, :, 1:1 + H]
+    xc = np.ascontiguousarray(xb_full[:, :, 1:1 + H])
+    rng = np.random.default_rng(6)
+    k = 41
+    keep = np.stack([[np.sort(rng.choice(T, k, replace=False)) for _ in range(H)] for _ in range(L)]).astype(np.int32)
+    og = oracle.quantize_asym(xc, bits, group, keep_idx=keep, Tp=48)
+    qg = kvp.alloc_qplane(L, k, H, D, bits, group, DEV, asymmetric=True)
+    assert qg.Tp == 48
+    kvp.kvp_quantize(xv, qg, keep_idx=torch.from_numpy(keep).to(DEV))
+    bt, nb = workloads.make_block_table(T, bs, seed=10, spare=1)
+    pool = np.zeros((L, nb, bs, H, D), dtype=np.uint16)
+    btn = bt.numpy()
+    for t in range(T):
+        pool[:, btn[t // bs], t % bs] = xc[:, t]
+    src = kvp.PagedKV(bits_to_torch(pool, DEV), bt.to(DEV), T)
+    qpg = kvp.alloc_qplane(L, k, H, D, bits, group, DEV, asymmetric=True)
+    kvp.kvp_quantize(src, qpg, keep_idx=torch.from_numpy(keep).to(DEV))
+    torch.cuda.synchronize()
+    for q in (qg, qpg):
+        assert np.array_equal(q.codes.cpu().numpy(), og[0])
+        assert np.array_equal(q.scales.cpu().numpy().view(np.uint32), og[1].view(np.uint32))
+        assert np.array_equal(q.mins.cpu().numpy().view(np.uint32), og[2].view(np.uint32))
+
+
+@pytest.mark.parametrize("bits", [8, 4, 2])
+def test_asymmetric_scale_exact_for_many_ranges(bits):
+    # the kernel forms range / (2^bits - 1) without a division instruction: check scale, min and codes
+    # against the oracle's IEEE arithmetic for every finite bf16 maximum over a zero minimum and for
+    # 2^18 random (min, max) pairs whose difference has a full-width significand
+    kvp = _kvp()
+    _say("asym ranges", bits)
+    rng = np.random.default_rng(bits)
+    mags = np.arange(0, 0x7F00, dtype=np.uint16)
+    n_pairs = 1 << 18
+    n = len(mags) + n_pairs
+    T = (n + 7) // 8
+    xb = np.zeros((1, T, 8, 128), dtype=np.uint16)
+    flat = xb.reshape(-1, 128)
+    flat[:len(mags), 5] = mags                                              # group 0: min 0, max = every bf16
+    flat[:len(mags), 40] = mags | 0x8000                                    # group 1: max 0, min = every -bf16
+    e = rng.integers(100, 150, n_pairs).astype(np.uint16)                   # exponents near each other
+    hi = ((e << 7) | rng.integers(0, 128, n_pairs).astype(np.uint16))
+    lo = (((e - rng.integers(0, 9, n_pairs).astype(np.uint16)) << 7) | rng.integers(0, 128, n_pairs).astype(np.uint16))
+    sl = slice(len(mags), n)
+    flat[sl, :] = lo[:, None]                                               # every element at the minimum ...
+    flat[sl, 3::32] = hi[:, None]                                           # ... one maximum per 32 channels
+    flat[sl, 9::32] = (lo + 1)[:, None]                                     # and a near-minimum element
+    flat[sl, :64] |= 0x8000                                                 # first half negated: min = -hi
+    x = bits_to_torch(xb, DEV)
+    qp = kvp.alloc_qplane(1, T, 8, 128, bits, 32, DEV, asymmetric=True)
+    kvp.kvp_quantize(x, qp)
+    torch.cuda.synchronize()
+    oc, os_, om = oracle.quantize_asym(xb, bits, 32, Tp=qp.Tp)
+    assert np.array_equal(qp.scales.cpu().numpy().view(np.uint32), os_.view(np.uint32))
+    assert np.array_equal(qp.mins.cpu().numpy().view(np.uint32), om.view(np.uint32))
+    assert np.array_equal(qp.codes.cpu().numpy(), oc)
