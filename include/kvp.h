@@ -99,7 +99,7 @@ typedef struct {
  * otherwise slot i is token i, k is ignored and dst->T must equal the source
  * T.  Writes dst->codes and dst->scales in full, padding slots included.
  * With dst->mins != NULL the asymmetric variant is used instead (uniform quantization with a
- * zero point, all 2^bits levels): per group mn = min x, scale = fl32(fl32(max x - mn) / (2^bits - 1)),
+ * zero point, all 2^bits levels): per group mn = min x (a zero minimum or maximum is taken as +0), scale = fl32(fl32(max x - mn) / (2^bits - 1)),
  * code = clamp(rint(fl32(fl32(x - mn) / scale)), 0, 2^bits - 1) as an UNSIGNED field, mins = mn;
  * kvp_dequantize_paged then returns bf16_rne(fl32(fl32(code * scale) + mn)). */
 int32_t kvp_quantize(const kvp_view* src, const kvp_paged* src_paged, const int32_t* keep_idx, int64_t k,

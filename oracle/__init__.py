@@ -57,6 +57,12 @@ def lib():
         _lib.oracle_dequantize_paged_asym.restype = ctypes.c_int
         _lib.oracle_dequantize_paged_asym.argtypes = [_p, _p, _p, ctypes.c_int, ctypes.c_int, _i64, _i64, _i64, _i64,
                                                       _i64, _p, _i64, _i64, _p, _i64]
+        _lib.oracle_quantize_channel.restype = ctypes.c_int
+        _lib.oracle_quantize_channel.argtypes = [_p, _i64, _i64, _i64, _i64, _i64, _i64, _i64, _p, _i64,
+                                                 ctypes.c_int, ctypes.c_int, ctypes.c_int, _i64, _p, _p, _p]
+        _lib.oracle_dequantize_paged_channel.restype = ctypes.c_int
+        _lib.oracle_dequantize_paged_channel.argtypes = [_p, _p, _p, ctypes.c_int, ctypes.c_int, ctypes.c_int, _i64, _i64,
+                                                         _i64, _i64, _i64, _p, _i64, _i64, _p, _i64]
         _lib.oracle_score_tokens.restype = ctypes.c_int
         _lib.oracle_score_tokens.argtypes = [_p, _i64, _i64, _i64, _i64, _i64, _p, _i64, _i64, _i64, _i64,
                                              _i64, _i64, _i64, ctypes.c_int, ctypes.c_int, _p]
@@ -199,6 +205,45 @@ def dequantize_paged_asym(codes, scales, mins, bits: int, group: int, T: int, bl
     _check(lib().oracle_dequantize_paged_asym(_ptr(codes), _ptr(scales), _ptr(mins), bits, group, L, T, Tp, H, D,
                                               _ptr(block_table), num_blocks, bs, _ptr(pool), num_blocks * bs * H * D),
            "dequantize_paged_asym")
+    return pool
+
+
+def quantize_channel(x: np.ndarray, bits: int, group: int, keep_idx: np.ndarray | None = None, Tp: int | None = None,
+                     asym: bool = False):
+    """Per-channel grouping (groups of `group` token slots per channel) -> (codes u8 [L][Tp][H][D*bits/8],
+    scales f32 [L][ceil(Tp/group)][H][D], mins likewise or None)."""
+    x, sl, st, sh = _view4(x)
+    L, T, H, D = x.shape
+    k = 0
+    if keep_idx is not None:
+        keep_idx = np.ascontiguousarray(keep_idx, dtype=np.int32)
+        k = keep_idx.shape[2]
+    n_slots = k if keep_idx is not None else T
+    if Tp is None:
+        Tp = n_slots
+    ng = (Tp + group - 1) // group
+    codes = np.full((L, Tp, H, D * bits // 8), 0xAB, dtype=np.uint8)
+    scales = np.full((L, ng, H, D), np.nan, dtype=np.float32)
+    mins = np.full((L, ng, H, D), np.nan, dtype=np.float32) if asym else None
+    _check(lib().oracle_quantize_channel(_ptr(x), L, T, H, D, sl, st, sh, _ptr(keep_idx), k, bits, group, int(asym), Tp,
+                                         _ptr(codes), _ptr(scales), _ptr(mins)), "quantize_channel")
+    return codes, scales, mins
+
+
+def dequantize_paged_channel(codes, scales, mins, bits: int, group: int, T: int, block_table, num_blocks: int, bs: int,
+                             pool: np.ndarray | None = None, fill: int = 0x7FC0):
+    codes = np.ascontiguousarray(codes)
+    scales = np.ascontiguousarray(scales, dtype=np.float32)
+    if mins is not None:
+        mins = np.ascontiguousarray(mins, dtype=np.float32)
+    L, Tp, H, cb = codes.shape
+    D = cb * 8 // bits
+    block_table = np.ascontiguousarray(block_table, dtype=np.int32)
+    if pool is None:
+        pool = np.full((L, num_blocks, bs, H, D), fill, dtype=np.uint16)
+    _check(lib().oracle_dequantize_paged_channel(_ptr(codes), _ptr(scales), _ptr(mins), bits, group, int(mins is not None),
+                                                 L, T, Tp, H, D, _ptr(block_table), num_blocks, bs, _ptr(pool),
+                                                 num_blocks * bs * H * D), "dequantize_paged_channel")
     return pool
 
 

@@ -147,7 +147,8 @@ void quantize_row_asym(const uint16_t* x, int64_t D, int bits, int group, uint8_
       mn = std::min(mn, v);
       mx = std::max(mx, v);
     }
-    if (mn == 0.0f) mn = 0.0f;  // -0 and +0 compare equal: store +0 so the bytes are unique
+    if (mn == 0.0f) mn = 0.0f;  // -0 and +0 compare equal: a zero extreme is taken as +0, so that the
+    if (mx == 0.0f) mx = 0.0f;  // stored minimum and a zero range (hence scale) have unique bytes
     const float range = mx - mn;
     const float scale = range / static_cast<float>(levels);
     scales[g0 / group] = scale;
@@ -393,6 +394,112 @@ int oracle_dequantize_paged_asym(const uint8_t* codes, const float* scales, cons
         uint16_t* row = pool + l * pool_stride_l + ((blk * bs + t % bs) * H + h) * D;
         dequantize_row_asym(codes + r * cb, scales + r * ns, mins + r * ns, D, bits, group, row);
       }
+    }
+  return 0;
+}
+
+// Per-channel grouping (the KIVI-style key quantizer the paper's Related work names): a group is
+// `group` consecutive token slots of ONE channel of one head, instead of `group` channels of one
+// token.  Slots are tokens, or kept tokens when a keep list is given; the last group of a plane
+// holds the n_slots % group remaining slots and padding slots never enter a minimum or maximum.
+// The per-element formulas are those of quantize_row (asym == 0) and quantize_row_asym (asym != 0).
+//   codes  [L][Tp][H][D*bits/8]   (same plane as the per-token codec)
+//   scales [L][ceil(Tp/group)][H][D], mins likewise (asym only)
+int oracle_quantize_channel(const uint16_t* x, int64_t L, int64_t T, int64_t H, int64_t D, int64_t stride_l,
+                            int64_t stride_t, int64_t stride_h, const int32_t* keep_idx, int64_t k, int bits,
+                            int group, int asym, int64_t Tp, uint8_t* codes, float* scales, float* mins) {
+  if (!x || !codes || !scales || (asym && !mins)) return -1;
+  if ((bits != 8 && bits != 4 && bits != 2) || group <= 0 || D <= 0 || (D * bits) % 8 != 0) return -1;
+  const int64_t n_slots = keep_idx ? k : T;
+  if (n_slots < 0 || n_slots > Tp || L < 0 || T < 0 || H <= 0) return -1;
+  const int64_t cb = D * bits / 8, n_groups = (Tp + group - 1) / group;
+  const int per_byte = 8 / bits;
+  const uint32_t field_mask = (1u << bits) - 1u;
+  const int qmax = qmax_of(bits), levels = (1 << bits) - 1;
+  const View v{x, stride_l, stride_t, stride_h};
+  std::memset(codes, 0, static_cast<size_t>(L * Tp * H * cb));
+  for (int64_t l = 0; l < L; ++l)
+    for (int64_t g = 0; g < n_groups; ++g)
+      for (int64_t h = 0; h < H; ++h)
+        for (int64_t c = 0; c < D; ++c) {
+          const int64_t i0 = g * group, i1 = std::min<int64_t>(i0 + group, n_slots);
+          std::vector<float> member;
+          for (int64_t i = i0; i < i1; ++i) {
+            int64_t t = i;
+            if (keep_idx) {
+              t = keep_idx[(l * H + h) * k + i];
+              if (t < 0 || t >= T) return -1;
+            }
+            member.push_back(bf16_to_f32(v.row(l, t, h)[c]));
+          }
+          float scale = 0.0f, mn = 0.0f;
+          if (!member.empty()) {
+            if (asym) {
+              float mx = member[0];
+              mn = member[0];
+              for (float f : member) {
+                mn = std::min(mn, f);
+                mx = std::max(mx, f);
+              }
+              if (mn == 0.0f) mn = 0.0f;  // a zero extreme is taken as +0
+              if (mx == 0.0f) mx = 0.0f;
+              const float range = mx - mn;
+              scale = range / static_cast<float>(levels);
+            } else {
+              float amax = 0.0f;
+              for (float f : member) amax = std::max(amax, std::fabs(f));
+              scale = amax / static_cast<float>(qmax);
+            }
+          }
+          const int64_t so = ((l * n_groups + g) * H + h) * D + c;
+          scales[so] = scale;
+          if (asym) mins[so] = mn;
+          for (size_t j = 0; j < member.size(); ++j) {
+            int q = 0;
+            if (scale != 0.0f) {
+              if (asym) {
+                const float d = member[j] - mn;
+                q = static_cast<int>(std::rint(d / scale));
+                q = std::min(levels, std::max(0, q));
+              } else {
+                q = static_cast<int>(std::rint(member[j] / scale));
+                q = std::min(qmax, std::max(-qmax, q));
+              }
+            }
+            const int64_t i = i0 + static_cast<int64_t>(j);
+            uint8_t* byte = codes + ((l * Tp + i) * H + h) * cb + c / per_byte;
+            *byte = static_cast<uint8_t>(*byte | ((static_cast<uint32_t>(q) & field_mask) << (bits * (c % per_byte))));
+          }
+        }
+  return 0;
+}
+
+// Inverse of oracle_quantize_channel into the paged pool: y = bf16_rne(q * scale) or, asym,
+// bf16_rne(fl32(fl32(q * scale) + mn)), with the scale (and minimum) of slot t's group and channel.
+int oracle_dequantize_paged_channel(const uint8_t* codes, const float* scales, const float* mins, int bits, int group,
+                                    int asym, int64_t L, int64_t T, int64_t Tp, int64_t H, int64_t D,
+                                    const int32_t* block_table, int64_t num_blocks, int64_t bs, uint16_t* pool,
+                                    int64_t pool_stride_l) {
+  if (!codes || !scales || (asym && !mins) || !block_table || !pool || bs <= 0 || T > Tp || group <= 0) return -1;
+  if ((bits != 8 && bits != 4 && bits != 2) || D <= 0 || (D * bits) % 8 != 0) return -1;
+  const int64_t cb = D * bits / 8, n_groups = (Tp + group - 1) / group;
+  const int per_byte = 8 / bits;
+  const uint32_t field_mask = (1u << bits) - 1u;
+  const int sign_bit = 1 << (bits - 1);
+  for (int64_t l = 0; l < L; ++l)
+    for (int64_t t = 0; t < T; ++t) {
+      const int64_t blk = block_table[t / bs];
+      if (blk < 0 || blk >= num_blocks) return -1;
+      for (int64_t h = 0; h < H; ++h)
+        for (int64_t c = 0; c < D; ++c) {
+          const uint8_t byte = codes[((l * Tp + t) * H + h) * cb + c / per_byte];
+          int q = static_cast<int>((byte >> (bits * (c % per_byte))) & field_mask);
+          if (!asym && (q & sign_bit)) q -= (1 << bits);
+          const int64_t so = ((l * n_groups + t / group) * H + h) * D + c;
+          float y = static_cast<float>(q) * scales[so];
+          if (asym) y = y + mins[so];
+          pool[l * pool_stride_l + ((blk * bs + t % bs) * H + h) * D + c] = f32_to_bf16_rne(y);
+        }
     }
   return 0;
 }

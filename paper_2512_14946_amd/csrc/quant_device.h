@@ -101,7 +101,7 @@ struct AsymQuantizer {
   bool unsafe;
   __device__ __forceinline__ AsymQuantizer(float gmin, float gmax) {
     mn = gmin + 0.0f;                                   // -0 -> +0, everything else unchanged
-    const float range = gmax - mn;
+    const float range = (gmax + 0.0f) - mn;             // a zero maximum counts as +0 too
     // range / LEVELS, correctly rounded without a division: product with the rounded reciprocal,
     // exact remainder, one correction (checked against IEEE division for all 2^23 significands and
     // LEVELS = 3, 15, 255).  Outside the exponent range where no step under- or overflows: divide.

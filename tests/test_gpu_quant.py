@@ -181,6 +181,11 @@ def _asym_special_rows(D=128):
         rows.append(r * 0.375)
     rows.append(np.full(D, 1.5))                                           # constant group: range 0
     rows.append(np.where(np.arange(D) % 2 == 0, 0.0, -0.0))                # +0 / -0 only
+    rows.append(np.where(np.arange(D) % 2 == 0, -0.0, 0.0))                # -0 first
+    rows.append(np.full(D, -0.0))                                          # -0 only: min, range, scale all +0
+    r = -np.abs(rng.standard_normal(D))
+    r[3::8] = -0.0                                                         # maximum is a negative zero
+    rows.append(r)
     rows.append(np.abs(rng.standard_normal(D)) + 100.0)                    # far from zero: x - min is exact, range small
     rows.append(-np.abs(rng.standard_normal(D)) * 2.0 ** 40)               # all negative, large
     r = rng.standard_normal(D) * 2.0 ** -8
