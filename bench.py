@@ -244,8 +244,11 @@ def side_measurements(kvp, workloads, torch, dev, K8, V8):
     L, T, H, D = K8.shape
     bt, nb = workloads.make_block_table(T, 16, seed=0, device=dev)
     for name, bits, group in [("int8_g128", 8, 128), ("int2_g32", 2, 32), ("int4_g32", 4, 32),
-                              ("asymmetric_int4_g64", 4, 64), ("asymmetric_int2_g32", 2, 32)]:
-        qp = kvp.alloc_qplane(L, T, H, D, bits, group, dev, asymmetric=name.startswith("asymmetric"))
+                              ("asymmetric_int4_g64", 4, 64), ("asymmetric_int2_g32", 2, 32),
+                              ("per_channel_int4_g32", 4, 32), ("per_channel_int4_g128", 4, 128),
+                              ("per_channel_asymmetric_int2_g32", 2, 32), ("per_channel_asymmetric_int2_g128", 2, 128)]:
+        qp = kvp.alloc_qplane(L, T, H, D, bits, group, dev, asymmetric="asymmetric" in name,
+                              per_channel=name.startswith("per_channel"))
         pg = kvp.alloc_paged(L, T, H, D, bt, nb, 16)
         tq = _time_loop(torch, lambda: kvp.kvp_quantize(K8, qp), 10, warm=2)
         td = _time_loop(torch, lambda: kvp.kvp_dequantize_paged(qp, pg), 10, warm=2)

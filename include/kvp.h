@@ -75,7 +75,15 @@ typedef struct {
   float* mins;    /* NULL: symmetric codec.  Else device [L][Tp][H][D/group]: asymmetric codec (see kvp_quantize) */
   int32_t bits, group;
   int64_t L, T, Tp, H, D;
+  int32_t group_axis; /* KVP_GROUP_CHANNELS (0) or KVP_GROUP_TOKENS (1), see kvp_quantize */
 } kvp_qplane;
+
+/* What a quantization group runs over.  KVP_GROUP_CHANNELS: `group` consecutive channels of one
+ * token (the layouts above).  KVP_GROUP_TOKENS: `group` consecutive slots of ONE channel of one
+ * head ("per-channel" key quantization); scales (and mins) are then device
+ * [L][ceil(Tp/group)][H][D], the codes plane is unchanged, the last group of a plane holds the
+ * T % group remaining slots, and padding slots never enter a minimum or maximum. */
+enum { KVP_GROUP_CHANNELS = 0, KVP_GROUP_TOKENS = 1 };
 
 /* One candidate configuration of the utility table: quantization (bits = 16
  * means none; group is then ignored) and the number of tokens kept
@@ -101,7 +109,10 @@ typedef struct {
  * With dst->mins != NULL the asymmetric variant is used instead (uniform quantization with a
  * zero point, all 2^bits levels): per group mn = min x (a zero minimum or maximum is taken as +0), scale = fl32(fl32(max x - mn) / (2^bits - 1)),
  * code = clamp(rint(fl32(fl32(x - mn) / scale)), 0, 2^bits - 1) as an UNSIGNED field, mins = mn;
- * kvp_dequantize_paged then returns bf16_rne(fl32(fl32(code * scale) + mn)). */
+ * kvp_dequantize_paged then returns bf16_rne(fl32(fl32(code * scale) + mn)).
+ * With dst->group_axis == KVP_GROUP_TOKENS the same formulas apply to groups of dst->group slots
+ * of one channel (Related work: KIVI / KVQuant style per-channel key quantizers); group is 32, 64
+ * or 128 slots, slots being kept tokens when keep_idx is given. */
 int32_t kvp_quantize(const kvp_view* src, const kvp_paged* src_paged, const int32_t* keep_idx, int64_t k,
                      const kvp_qplane* dst, void* stream);
 
@@ -110,7 +121,9 @@ int32_t kvp_quantize(const kvp_view* src, const kvp_paged* src_paged, const int3
  *     pool[l][block_table[t/bs]][t%bs][h][c] = bf16_rne((float)code * scale)
  * (one binary32 multiply, then round-to-nearest-even to bf16).  Page slots at
  * or beyond T and blocks the table does not name are not written.  dst->T
- * must equal src->T; L, H, D must match. */
+ * must equal src->T; L, H, D must match.  Planes grouped along tokens
+ * (KVP_GROUP_TOKENS) need src->group to be a multiple of dst->bs, so that a
+ * page lies inside one group (KVP_ERR_UNSUPPORTED otherwise). */
 int32_t kvp_dequantize_paged(const kvp_qplane* src, const kvp_paged* dst, void* stream);
 
 /* Attention-score token importance (Evaluation, Baselines: snapkv "computes

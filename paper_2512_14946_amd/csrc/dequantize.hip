@@ -11,6 +11,8 @@
 // (nearest even) on the integer pattern, so the output is bit-identical to the definition.
 
 #include "kvp_common.h"
+#include "kvp_internal.h"
+#include "quant_device.h"
 
 namespace kvp {
 namespace {
@@ -18,43 +20,6 @@ namespace {
 constexpr int kThreads = 256;
 constexpr int kRowsPerStep = kThreads / kLanesPerRow;  // 16
 constexpr int kUnroll = 8;                             // a 16-token x 8-head page in one sweep
-
-struct DequantArgs {
-  const uint8_t* codes;
-  const float* scales;
-  const float* mins;   // asymmetric codec only
-  uint16_t* pool;
-  const int32_t* block_table;
-  int64_t pool_stride_l;   // elements
-  int64_t Tp;
-  uint32_t T, H, bs, num_blocks;
-};
-
-template <int BITS>
-__device__ __forceinline__ uint2 load_codes(const uint8_t* row_codes, int lane_in_row);
-template <>
-__device__ __forceinline__ uint2 load_codes<8>(const uint8_t* row_codes, int lane_in_row) {
-  return load_stream8(row_codes + lane_in_row * 8);
-}
-template <>
-__device__ __forceinline__ uint2 load_codes<4>(const uint8_t* row_codes, int lane_in_row) {
-  return make_uint2(load_stream4(row_codes + lane_in_row * 4), 0);
-}
-template <>
-__device__ __forceinline__ uint2 load_codes<2>(const uint8_t* row_codes, int lane_in_row) {
-  return make_uint2(load_stream2(row_codes + lane_in_row * 2), 0);
-}
-
-// field i (of 8) of a lane's packed codes: signed (symmetric codec) or unsigned (asymmetric codec)
-template <int BITS, bool ASYM>
-__device__ __forceinline__ int field(const uint2 c, int i) {
-  const uint32_t w = (BITS == 8 && i >= 4) ? c.y : c.x;
-  const int off = BITS == 8 ? 8 * (i & 3) : BITS * i;
-  if constexpr (ASYM)
-    return static_cast<int>(__builtin_amdgcn_ubfe(w, off, BITS));
-  else
-    return __builtin_amdgcn_sbfe(static_cast<int>(w), off, BITS);
-}
 
 template <int BITS, int GROUP, bool ASYM>
 __global__ __launch_bounds__(kThreads) void dequantize_paged_kernel(const DequantArgs a) {
@@ -160,6 +125,11 @@ extern "C" int32_t kvp_dequantize_paged(const kvp_qplane* src, const kvp_paged* 
   a.num_blocks = static_cast<uint32_t>(dst->num_blocks);
   const dim3 grid(static_cast<unsigned>(ceil_div(dst->T, dst->bs)), static_cast<unsigned>(dst->L));
   const hipStream_t st = as_stream(stream);
+  if (src->group_axis == KVP_GROUP_TOKENS) {
+    if (src->group % dst->bs != 0) return KVP_ERR_UNSUPPORTED;
+    dequantize_channel_launch(a, src->bits, src->group, dst->L, st);
+    return launch_status();
+  }
   switch (src->bits) {
     case 8: launch_group<8>(src->group, grid, st, a); break;
     case 4: launch_group<4>(src->group, grid, st, a); break;

@@ -55,6 +55,7 @@ inline int32_t check_qplane(const kvp_qplane* q) {
   if (q->D != kHeadDim) return KVP_ERR_UNSUPPORTED;
   if (q->bits != 8 && q->bits != 4 && q->bits != 2) return KVP_ERR_UNSUPPORTED;
   if (q->group != 32 && q->group != 64 && q->group != 128) return KVP_ERR_UNSUPPORTED;
+  if (q->group_axis != KVP_GROUP_CHANNELS && q->group_axis != KVP_GROUP_TOKENS) return KVP_ERR_UNSUPPORTED;
   if (q->L <= 0 || q->T <= 0 || q->H <= 0 || q->Tp < q->T) return KVP_ERR_SHAPE;
   if (!aligned16(q->codes) || !aligned16(q->scales) || !aligned16(q->mins)) return KVP_ERR_ALIGN;
   return KVP_OK;

@@ -236,4 +236,52 @@ __device__ __forceinline__ uint32_t pack_uint2x8(const float q[8]) {
   return static_cast<uint32_t>(s);
 }
 
+// ---- packed codes of one lane (8 consecutive channels of a row) ----------------------------------
+template <int BITS>
+struct Packed;  // the 8 codes of one lane
+template <> struct Packed<8> { uint32_t lo, hi; };
+template <> struct Packed<4> { uint32_t w; };
+template <> struct Packed<2> { uint32_t w; };
+
+template <int BITS>
+__device__ __forceinline__ void store_codes(uint8_t* row_codes, int lane_in_row, const Packed<BITS>& p);
+template <>
+__device__ __forceinline__ void store_codes<8>(uint8_t* row_codes, int lane_in_row, const Packed<8>& p) {
+  store_stream8(row_codes + lane_in_row * 8, make_uint2(p.lo, p.hi));
+}
+template <>
+__device__ __forceinline__ void store_codes<4>(uint8_t* row_codes, int lane_in_row, const Packed<4>& p) {
+  store_stream4(row_codes + lane_in_row * 4, p.w);
+}
+template <>
+__device__ __forceinline__ void store_codes<2>(uint8_t* row_codes, int lane_in_row, const Packed<2>& p) {
+  store_stream2(row_codes + lane_in_row * 2, p.w);
+}
+
+template <int BITS>
+__device__ __forceinline__ uint2 load_codes(const uint8_t* row_codes, int lane_in_row);
+template <>
+__device__ __forceinline__ uint2 load_codes<8>(const uint8_t* row_codes, int lane_in_row) {
+  return load_stream8(row_codes + lane_in_row * 8);
+}
+template <>
+__device__ __forceinline__ uint2 load_codes<4>(const uint8_t* row_codes, int lane_in_row) {
+  return make_uint2(load_stream4(row_codes + lane_in_row * 4), 0);
+}
+template <>
+__device__ __forceinline__ uint2 load_codes<2>(const uint8_t* row_codes, int lane_in_row) {
+  return make_uint2(load_stream2(row_codes + lane_in_row * 2), 0);
+}
+
+// field i (of 8) of a lane's packed codes: signed (symmetric codec) or unsigned (asymmetric codec)
+template <int BITS, bool ASYM>
+__device__ __forceinline__ int field(const uint2 c, int i) {
+  const uint32_t w = (BITS == 8 && i >= 4) ? c.y : c.x;
+  const int off = BITS == 8 ? 8 * (i & 3) : BITS * i;
+  if constexpr (ASYM)
+    return static_cast<int>(__builtin_amdgcn_ubfe(w, off, BITS));
+  else
+    return __builtin_amdgcn_sbfe(static_cast<int>(w), off, BITS);
+}
+
 }  // namespace kvp

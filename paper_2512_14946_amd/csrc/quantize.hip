@@ -11,6 +11,7 @@
 // The exact-code arithmetic (reciprocal fast path with an exact fallback) lives in quant_device.h.
 
 #include "kvp_common.h"
+#include "kvp_internal.h"
 #include "quant_device.h"
 
 namespace kvp {
@@ -21,46 +22,6 @@ constexpr int kRowsPerStep = kThreads / kLanesPerRow;  // 16 rows per load step
 // Rows in flight per thread, chosen by measurement on the 8B-shaped plane: the int4 kernel sustains
 // 76 % of the HBM peak with 4 (75 % with 2), int8 and int2 80 % and 82 % with 2 (77 % and 79 % with 4).
 constexpr int steps_for(int bits) { return bits == 4 ? 4 : 2; }
-
-enum SrcMode { kLinear = 0, kStrided = 1, kPaged = 2 };
-
-struct QuantArgs {
-  const uint16_t* src;         // view base or page pool
-  int64_t stride_l, stride_t, stride_h;  // elements (view); stride_l also for the pool
-  const int32_t* block_table;  // paged source only
-  const int32_t* keep_idx;     // [L][H][k] or null
-  int64_t k;                   // row length of keep_idx
-  uint32_t n_slots;            // valid slots per layer (T, or k when gathered)
-  uint32_t T;                  // source tokens per layer
-  uint32_t num_blocks;         // paged source only
-  uint32_t rows_per_layer;     // Tp * H
-  uint32_t H, bs;
-  FastDiv div_h, div_bs;
-  uint8_t* codes;
-  float* scales;
-  float* mins;   // asymmetric codec only
-};
-
-template <int BITS>
-struct Packed;  // the 8 codes of one lane
-template <> struct Packed<8> { uint32_t lo, hi; };
-template <> struct Packed<4> { uint32_t w; };
-template <> struct Packed<2> { uint32_t w; };
-
-template <int BITS>
-__device__ __forceinline__ void store_codes(uint8_t* row_codes, int lane_in_row, const Packed<BITS>& p);
-template <>
-__device__ __forceinline__ void store_codes<8>(uint8_t* row_codes, int lane_in_row, const Packed<8>& p) {
-  store_stream8(row_codes + lane_in_row * 8, make_uint2(p.lo, p.hi));
-}
-template <>
-__device__ __forceinline__ void store_codes<4>(uint8_t* row_codes, int lane_in_row, const Packed<4>& p) {
-  store_stream4(row_codes + lane_in_row * 4, p.w);
-}
-template <>
-__device__ __forceinline__ void store_codes<2>(uint8_t* row_codes, int lane_in_row, const Packed<2>& p) {
-  store_stream2(row_codes + lane_in_row * 2, p.w);
-}
 
 template <int BITS, int GROUP, bool ASYM>
 __device__ __forceinline__ void quantize_lane(const uint4 raw, Packed<BITS>& out, float& scale_out, float& min_out) {
@@ -252,9 +213,13 @@ extern "C" int32_t kvp_quantize(const kvp_view* src, const kvp_paged* src_paged,
   a.codes = dst->codes;
   a.scales = dst->scales;
   a.mins = dst->mins;
+  const hipStream_t st = as_stream(stream);
+  if (dst->group_axis == KVP_GROUP_TOKENS) {
+    quantize_channel_launch(a, dst->bits, dst->group, mode, L, st);
+    return launch_status();
+  }
   const int rows_per_block = kRowsPerStep * steps_for(dst->bits);
   const dim3 grid(static_cast<unsigned>(ceil_div(a.rows_per_layer, rows_per_block)), static_cast<unsigned>(L));
-  const hipStream_t st = as_stream(stream);
   switch (dst->bits) {
     case 8: launch_group<8>(dst->group, mode, grid, st, a); break;
     case 4: launch_group<4>(dst->group, mode, grid, st, a); break;

@@ -36,7 +36,7 @@ class _Paged(ctypes.Structure):
 
 class _QPlane(ctypes.Structure):
     _fields_ = [("codes", _vp), ("scales", _vp), ("mins", _vp), ("bits", _i32), ("group", _i32),
-                ("L", _i64), ("T", _i64), ("Tp", _i64), ("H", _i64), ("D", _i64)]
+                ("L", _i64), ("T", _i64), ("Tp", _i64), ("H", _i64), ("D", _i64), ("group_axis", _i32)]
 
 
 class _Tier(ctypes.Structure):
@@ -105,13 +105,15 @@ _lib = _load()
 
 @dataclass
 class QPlane:
-    """Compressed plane: codes u8 [L][Tp][H][D*bits/8], scales f32 [L][Tp][H][D/group]."""
+    """Compressed plane: codes u8 [L][Tp][H][D*bits/8], scales f32 [L][Tp][H][D/group]
+    (group_axis 0: groups of channels) or [L][ceil(Tp/group)][H][D] (group_axis 1: groups of token slots)."""
     codes: torch.Tensor
     scales: torch.Tensor
     bits: int
     group: int
     T: int
     mins: torch.Tensor | None = None   # set: asymmetric codec (unsigned codes, per-group minimum)
+    group_axis: int = 0                # KVP_GROUP_CHANNELS = 0, KVP_GROUP_TOKENS = 1
 
     @property
     def Tp(self) -> int:
@@ -130,12 +132,13 @@ class PagedKV:
 
 
 def alloc_qplane(L: int, T: int, H: int, D: int, bits: int, group: int, device, page: int = 16,
-                 asymmetric: bool = False) -> QPlane:
+                 asymmetric: bool = False, per_channel: bool = False) -> QPlane:
     Tp = (T + page - 1) // page * page
     codes = torch.empty(L, Tp, H, D * bits // 8, dtype=torch.uint8, device=device)
-    scales = torch.empty(L, Tp, H, D // group, dtype=torch.float32, device=device)
-    mins = torch.empty(L, Tp, H, D // group, dtype=torch.float32, device=device) if asymmetric else None
-    return QPlane(codes, scales, bits, group, T, mins)
+    sshape = (L, (Tp + group - 1) // group, H, D) if per_channel else (L, Tp, H, D // group)
+    scales = torch.empty(sshape, dtype=torch.float32, device=device)
+    mins = torch.empty(sshape, dtype=torch.float32, device=device) if asymmetric else None
+    return QPlane(codes, scales, bits, group, T, mins, int(per_channel))
 
 
 def alloc_paged(L: int, T: int, H: int, D: int, block_table: torch.Tensor, num_blocks: int, bs: int = 16,
@@ -192,14 +195,15 @@ def _qplane(q: QPlane) -> _QPlane:
         raise ValueError("codes and scales must be contiguous")
     L, Tp, H, cb = q.codes.shape
     D = cb * 8 // q.bits
-    if tuple(q.scales.shape) != (L, Tp, H, D // q.group):
+    want = (L, (Tp + q.group - 1) // q.group, H, D) if q.group_axis == 1 else (L, Tp, H, D // q.group)
+    if tuple(q.scales.shape) != want:
         raise ValueError("scales shape does not match codes")
     mins = None
     if q.mins is not None:
         if q.mins.dtype != torch.float32 or not q.mins.is_contiguous() or tuple(q.mins.shape) != tuple(q.scales.shape):
             raise ValueError("mins must be contiguous float32 with the shape of scales")
         mins = q.mins.data_ptr()
-    return _QPlane(q.codes.data_ptr(), q.scales.data_ptr(), mins, q.bits, q.group, L, q.T, Tp, H, D)
+    return _QPlane(q.codes.data_ptr(), q.scales.data_ptr(), mins, q.bits, q.group, L, q.T, Tp, H, D, q.group_axis)
 
 
 def _check(rc: int, what: str):
