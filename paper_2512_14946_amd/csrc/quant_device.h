@@ -59,6 +59,10 @@ struct GroupQuantizer {
     unsafe = !(scale >= 0x1p-100f && scale <= 0x1p100f) && scale != 0.0f;
     inv = (scale == 0.0f) ? 0.0f : __builtin_amdgcn_rcpf(scale);
   }
+  // from parameters computed elsewhere (the same scale and reciprocal)
+  __device__ __forceinline__ GroupQuantizer(float s, float i) : scale(s), inv(i) {
+    unsafe = !(s >= 0x1p-100f && s <= 0x1p100f) && s != 0.0f;
+  }
   // |y0 - fl32(x/scale)| <= |x/scale| * (2^-22 + 2^-24 + 2^-24) < (QMAX + 1) * 2^-21
   static constexpr float kTieMargin = static_cast<float>(QMAX + 1) * 0x1p-20f;
 
@@ -116,6 +120,10 @@ struct AsymQuantizer {
     unsafe = unsafe && scale != 0.0f;
     inv = (scale == 0.0f) ? 0.0f : __builtin_amdgcn_rcpf(scale);
   }
+  // from parameters computed elsewhere (the same scale, reciprocal and minimum)
+  __device__ __forceinline__ AsymQuantizer(float s, float i, float m) : scale(s), inv(i), mn(m) {
+    unsafe = !(s >= 0x1p-100f && s <= 0x1p100f) && s != 0.0f;
+  }
   static constexpr float kTieMargin = static_cast<float>(LEVELS + 1) * 0x1p-20f;
 
   __device__ __forceinline__ float code(float x) const {
@@ -171,6 +179,9 @@ struct TernaryQuantizer {
   __device__ __forceinline__ explicit TernaryQuantizer(float a) : amax(a) {
     unsafe = !(a >= 0x1p-100f && a <= 0x1p100f) && a != 0.0f;
     inv = (a == 0.0f) ? 0.0f : __builtin_amdgcn_rcpf(a) * (1.0f - 0x1p-20f);
+  }
+  __device__ __forceinline__ TernaryQuantizer(float a, float i) : amax(a), inv(i) {
+    unsafe = !(a >= 0x1p-100f && a <= 0x1p100f) && a != 0.0f;
   }
   __device__ __forceinline__ void codes8(const float x[8], float q[8]) const {
 #pragma unroll

@@ -4,12 +4,14 @@
 // in quant_device.h; only the set of elements that share a scale differs: `group` consecutive slots
 // of one channel of one head.
 //
-// Quantize.  A 1024-thread block owns one (token group, tile of HB heads, layer).  A thread owns one
-// (head, 8-channel chunk) column and the token slots  slot, slot + S, ... of the group
-// (S = 1024 / (16 HB) slots are loaded per step, so one step of the block reads S tokens x HB heads:
-// one contiguous run of a flat plane).  All G / S rows of a thread are loaded up front and stay in
-// registers; the per-channel extremes of the S slots meet in LDS (one barrier), every thread then
-// builds the 8 quantizers of its channels and encodes its own rows.  The plane is read once.
+// Quantize.  A 256-thread block owns one (token group, tile of HB heads, layer), HB = 2 or 1.  A
+// thread owns one (head, 8-channel chunk) column and the token slots  slot, slot + S, ...  of the
+// group (S = 256 / (16 HB) slots per load step).  All G / S rows of a thread (4 or 8) are loaded up
+// front and stay in registers, so the plane is read once.  The per-channel extremes of the S slots
+// meet in LDS; one thread per channel then reduces them and builds that channel's quantizer (scale,
+// reciprocal, minimum) once, publishes it to LDS and to the scales / mins planes; after the second
+// barrier every thread encodes its own rows with the 8 quantizers of its channels.  Blocks are small
+// on purpose: several are resident per CU, so one block's load phase overlaps another's encode.
 //
 // Dequantize.  One 256-thread block per (page, layer) as in the per-token kernel; a page lies inside
 // one token group, so a lane keeps the 8 scales (and minima) of its channels in registers.
@@ -21,15 +23,17 @@
 namespace kvp {
 namespace {
 
-constexpr int kThreadsQ = 1024;
-
+// Quantizer of one channel's group, built from the group's extremes (parameter phase) or rebuilt
+// from the published (scale, reciprocal, minimum) in the encode phase.
 template <int BITS, bool ASYM>
-struct ChannelQuantizer;   // quantizer of one channel's group
+struct ChannelQuantizer;
 template <int BITS>
 struct ChannelQuantizer<BITS, true> {
   AsymQuantizer<(1 << BITS) - 1> q;
   __device__ __forceinline__ ChannelQuantizer(float lo, float hi) : q(lo, hi) {}
+  __device__ __forceinline__ ChannelQuantizer(float scale, float inv, float mn) : q(scale, inv, mn) {}
   __device__ __forceinline__ float scale() const { return q.scale; }
+  __device__ __forceinline__ float inv() const { return q.inv; }
   __device__ __forceinline__ float minimum() const { return q.mn; }
   __device__ __forceinline__ bool unsafe() const { return q.unsafe; }
   __device__ __forceinline__ float fast(float x) const { return q.code(x); }
@@ -41,7 +45,9 @@ template <int BITS>
 struct ChannelQuantizer<BITS, false> {
   GroupQuantizer<(1 << (BITS - 1)) - 1> q;
   __device__ __forceinline__ ChannelQuantizer(float, float amax) : q(amax) {}
+  __device__ __forceinline__ ChannelQuantizer(float scale, float inv, float) : q(scale, inv) {}
   __device__ __forceinline__ float scale() const { return q.scale; }
+  __device__ __forceinline__ float inv() const { return q.inv; }
   __device__ __forceinline__ float minimum() const { return 0.0f; }
   __device__ __forceinline__ bool unsafe() const { return q.unsafe; }
   __device__ __forceinline__ float fast(float x) const { return q.code(x); }
@@ -51,7 +57,9 @@ template <>
 struct ChannelQuantizer<2, false> {
   TernaryQuantizer q;
   __device__ __forceinline__ ChannelQuantizer(float, float amax) : q(amax) {}
+  __device__ __forceinline__ ChannelQuantizer(float scale, float inv, float) : q(scale, inv) {}
   __device__ __forceinline__ float scale() const { return q.amax; }
+  __device__ __forceinline__ float inv() const { return q.inv; }
   __device__ __forceinline__ float minimum() const { return 0.0f; }
   __device__ __forceinline__ bool unsafe() const { return q.unsafe; }
   __device__ __forceinline__ float fast(float x) const { return rintf(x * q.inv); }
@@ -82,20 +90,43 @@ __device__ __forceinline__ Packed<BITS> zero_codes() {
   return p;
 }
 
-template <int BITS, int G, int HB, bool ASYM>
-__global__ __launch_bounds__(kThreadsQ) void quantize_channel_kernel(const QuantArgs a, const int mode) {
+// Block shape for a group of G slots: threads and heads per block; a thread keeps
+// G * 16 * HB / threads rows in registers.
+#ifndef KVP_QC_SHAPES
+#define KVP_QC_SHAPES {256, 2}, {256, 2}, {256, 1}
+#endif
+struct BlockShape { int threads, heads; };
+constexpr BlockShape kShapes[3] = {KVP_QC_SHAPES};   // G = 32, 64, 128
+constexpr BlockShape shape_for(int G) { return kShapes[G == 32 ? 0 : (G == 64 ? 1 : 2)]; }
+
+// LDS position of channel `ch` (0 .. 8*COLS-1, ch = col * 8 + c) in an array that the encode phase
+// reads back as two float4 per column with consecutive columns adjacent: [half][col][4].
+template <int COLS>
+__device__ __forceinline__ int param_slot(int ch) {
+  const int col = ch >> 3, c = ch & 7;
+  return ((c >> 2) * COLS + col) * 4 + (c & 3);
+}
+
+template <int BITS, int G, int HB, int kThreadsQ, bool ASYM>
+__global__ __launch_bounds__(kThreadsQ) void quantize_channel_kernel(const QuantArgs a, const int mode,
+                                                                     const uint32_t n_groups, const uint32_t n_tiles,
+                                                                     const FastDiv div_tiles) {
   constexpr int COLS = kLanesPerRow * HB;   // (head, 8-channel chunk) columns of the block
   constexpr int S = kThreadsQ / COLS;       // token slots per load step
   constexpr int NL = G / S;                 // rows per thread
+  constexpr int NCH = COLS * 8;             // channels of the block
   static_assert(NL >= 1 && NL * S == G, "group must be a multiple of the slots per step");
+  static_assert(NCH <= kThreadsQ, "one thread per channel in the parameter phase");
   constexpr int CB = kHeadDim * BITS / 8;
-  __shared__ float4 red_hi[S][2][COLS];
-  __shared__ float4 red_lo[ASYM ? S : 1][2][ASYM ? COLS : 1];
+  __shared__ __align__(16) float part_hi[S][NCH];                        // per slot and channel: max (or abs-max)
+  __shared__ __align__(16) float part_lo[ASYM ? S : 1][ASYM ? NCH : 4];  // and min
+  __shared__ float4 prm_scale[2 * COLS], prm_inv[2 * COLS], prm_min[ASYM ? 2 * COLS : 1];
 
   const uint32_t col = threadIdx.x % COLS, slot = threadIdx.x / COLS;
   const uint32_t lane16 = col % kLanesPerRow;
-  const uint32_t h = blockIdx.y * HB + col / kLanesPerRow;
-  const uint32_t g = blockIdx.x, l = blockIdx.z;
+  const uint32_t g = div_tiles.quot(blockIdx.x), tile = blockIdx.x - g * n_tiles;   // head tile fastest
+  const uint32_t h0 = tile * HB, h = h0 + col / kLanesPerRow;
+  const uint32_t l = blockIdx.y;
   const bool h_ok = h < a.H;
   const uint32_t i0 = g * G;
   const uint32_t Tp = a.rows_per_layer / a.H;
@@ -127,72 +158,86 @@ __global__ __launch_bounds__(kThreadsQ) void quantize_channel_kernel(const Quant
   }
 
   // ---- extremes of this thread's rows, per channel ----
-  float hi[8], lo[8];
+  {
+    float hi[8], lo[8];
 #pragma unroll
-  for (int c = 0; c < 8; ++c) {
-    hi[c] = ASYM ? -INFINITY : 0.0f;
-    lo[c] = INFINITY;
-  }
-#pragma unroll
-  for (int j = 0; j < NL; ++j) {
-    float x[8];
-    unpack_bf16x8(raw[j], x);
-    if constexpr (ASYM) {
-      if (i0 + j * S + slot < a.n_slots) {   // padding slots never enter a minimum or maximum
-#pragma unroll
-        for (int c = 0; c < 8; ++c) {
-          hi[c] = fmaxf(hi[c], x[c]);
-          lo[c] = fminf(lo[c], x[c]);
-        }
-      }
-    } else {
-#pragma unroll
-      for (int c = 0; c < 8; ++c) hi[c] = fmaxf(hi[c], fabsf(x[c]));
+    for (int c = 0; c < 8; ++c) {
+      hi[c] = ASYM ? -INFINITY : 0.0f;
+      lo[c] = INFINITY;
     }
-  }
-  red_hi[slot][0][col] = make_float4(hi[0], hi[1], hi[2], hi[3]);
-  red_hi[slot][1][col] = make_float4(hi[4], hi[5], hi[6], hi[7]);
-  if constexpr (ASYM) {
-    red_lo[slot][0][col] = make_float4(lo[0], lo[1], lo[2], lo[3]);
-    red_lo[slot][1][col] = make_float4(lo[4], lo[5], lo[6], lo[7]);
+#pragma unroll
+    for (int j = 0; j < NL; ++j) {
+      float x[8];
+      unpack_bf16x8(raw[j], x);
+      if constexpr (ASYM) {
+        if (i0 + j * S + slot < a.n_slots) {   // padding slots never enter a minimum or maximum
+#pragma unroll
+          for (int c = 0; c < 8; ++c) {
+            hi[c] = fmaxf(hi[c], x[c]);
+            lo[c] = fminf(lo[c], x[c]);
+          }
+        }
+      } else {
+#pragma unroll
+        for (int c = 0; c < 8; ++c) hi[c] = fmaxf(hi[c], fabsf(x[c]));
+      }
+    }
+    float4* ph = reinterpret_cast<float4*>(&part_hi[slot][col * 8]);
+    ph[0] = make_float4(hi[0], hi[1], hi[2], hi[3]);
+    ph[1] = make_float4(hi[4], hi[5], hi[6], hi[7]);
+    if constexpr (ASYM) {
+      float4* pl = reinterpret_cast<float4*>(&part_lo[slot][col * 8]);
+      pl[0] = make_float4(lo[0], lo[1], lo[2], lo[3]);
+      pl[1] = make_float4(lo[4], lo[5], lo[6], lo[7]);
+    }
   }
   __syncthreads();
-#pragma unroll 4
-  for (int s = 0; s < S; ++s) {
-    const float4 u0 = red_hi[s][0][col], u1 = red_hi[s][1][col];
-    hi[0] = fmaxf(hi[0], u0.x); hi[1] = fmaxf(hi[1], u0.y); hi[2] = fmaxf(hi[2], u0.z); hi[3] = fmaxf(hi[3], u0.w);
-    hi[4] = fmaxf(hi[4], u1.x); hi[5] = fmaxf(hi[5], u1.y); hi[6] = fmaxf(hi[6], u1.z); hi[7] = fmaxf(hi[7], u1.w);
-    if constexpr (ASYM) {
-      const float4 v0 = red_lo[s][0][col], v1 = red_lo[s][1][col];
-      lo[0] = fminf(lo[0], v0.x); lo[1] = fminf(lo[1], v0.y); lo[2] = fminf(lo[2], v0.z); lo[3] = fminf(lo[3], v0.w);
-      lo[4] = fminf(lo[4], v1.x); lo[5] = fminf(lo[5], v1.y); lo[6] = fminf(lo[6], v1.z); lo[7] = fminf(lo[7], v1.w);
+
+  // ---- one thread per channel: group extremes -> quantizer parameters, published to LDS and memory ----
+  using CQ = ChannelQuantizer<BITS, ASYM>;
+  if (threadIdx.x < NCH) {
+    const uint32_t ch = threadIdx.x;
+    float hi = part_hi[0][ch], lo = ASYM ? part_lo[0][ch] : 0.0f;
+#pragma unroll
+    for (int s = 1; s < S; ++s) {
+      hi = fmaxf(hi, part_hi[s][ch]);
+      if constexpr (ASYM) lo = fminf(lo, part_lo[s][ch]);
+    }
+    const uint32_t hc = h0 + ch / kHeadDim;   // head of this channel
+    if (ASYM && (hc >= a.H || i0 >= a.n_slots)) hi = lo = 0.0f;   // idle column, or a group of padding slots only
+    const CQ cq(lo, hi);
+    const int ps = param_slot<COLS>(ch);
+    reinterpret_cast<float*>(prm_scale)[ps] = cq.scale();
+    reinterpret_cast<float*>(prm_inv)[ps] = cq.inv();
+    if constexpr (ASYM) reinterpret_cast<float*>(prm_min)[ps] = cq.minimum();
+    if (hc < a.H) {
+      const int64_t so = ((static_cast<int64_t>(l) * n_groups + g) * a.H + hc) * kHeadDim + ch % kHeadDim;
+      a.scales[so] = cq.scale();
+      if constexpr (ASYM) a.mins[so] = cq.minimum();
     }
   }
-  if (ASYM && (!h_ok || i0 >= a.n_slots)) {   // a group of padding slots only (or an idle column): scale 0, minimum 0
-#pragma unroll
-    for (int c = 0; c < 8; ++c) hi[c] = lo[c] = 0.0f;
-  }
+  __syncthreads();
 
-  // ---- the 8 quantizers of this thread's channels; slot 0 publishes scales and minima ----
-  using CQ = ChannelQuantizer<BITS, ASYM>;
-  const CQ cq[8] = {CQ(lo[0], hi[0]), CQ(lo[1], hi[1]), CQ(lo[2], hi[2]), CQ(lo[3], hi[3]),
-                    CQ(lo[4], hi[4]), CQ(lo[5], hi[5]), CQ(lo[6], hi[6]), CQ(lo[7], hi[7])};
+  // ---- encode ----
+  float sc[8], iv[8], mn[8];
+  {
+    const float4 s0 = prm_scale[col], s1 = prm_scale[COLS + col], v0 = prm_inv[col], v1 = prm_inv[COLS + col];
+    sc[0] = s0.x; sc[1] = s0.y; sc[2] = s0.z; sc[3] = s0.w; sc[4] = s1.x; sc[5] = s1.y; sc[6] = s1.z; sc[7] = s1.w;
+    iv[0] = v0.x; iv[1] = v0.y; iv[2] = v0.z; iv[3] = v0.w; iv[4] = v1.x; iv[5] = v1.y; iv[6] = v1.z; iv[7] = v1.w;
+    if constexpr (ASYM) {
+      const float4 m0 = prm_min[col], m1 = prm_min[COLS + col];
+      mn[0] = m0.x; mn[1] = m0.y; mn[2] = m0.z; mn[3] = m0.w; mn[4] = m1.x; mn[5] = m1.y; mn[6] = m1.z; mn[7] = m1.w;
+    } else {
+#pragma unroll
+      for (int c = 0; c < 8; ++c) mn[c] = 0.0f;
+    }
+  }
+  const CQ cq[8] = {CQ(sc[0], iv[0], mn[0]), CQ(sc[1], iv[1], mn[1]), CQ(sc[2], iv[2], mn[2]), CQ(sc[3], iv[3], mn[3]),
+                    CQ(sc[4], iv[4], mn[4]), CQ(sc[5], iv[5], mn[5]), CQ(sc[6], iv[6], mn[6]), CQ(sc[7], iv[7], mn[7])};
   bool any_unsafe = false;
 #pragma unroll
   for (int c = 0; c < 8; ++c) any_unsafe = any_unsafe || cq[c].unsafe();
-  if (slot == 0 && h_ok) {
-    const int64_t so = ((static_cast<int64_t>(l) * gridDim.x + g) * a.H + h) * kHeadDim + lane16 * 8;
-    float4* sp = reinterpret_cast<float4*>(a.scales + so);
-    sp[0] = make_float4(cq[0].scale(), cq[1].scale(), cq[2].scale(), cq[3].scale());
-    sp[1] = make_float4(cq[4].scale(), cq[5].scale(), cq[6].scale(), cq[7].scale());
-    if constexpr (ASYM) {
-      float4* mp = reinterpret_cast<float4*>(a.mins + so);
-      mp[0] = make_float4(cq[0].minimum(), cq[1].minimum(), cq[2].minimum(), cq[3].minimum());
-      mp[1] = make_float4(cq[4].minimum(), cq[5].minimum(), cq[6].minimum(), cq[7].minimum());
-    }
-  }
 
-  // ---- encode ----
   uint8_t* codes_l = a.codes + static_cast<int64_t>(l) * a.rows_per_layer * CB;
 #pragma unroll
   for (int j = 0; j < NL; ++j) {
@@ -215,16 +260,11 @@ __global__ __launch_bounds__(kThreadsQ) void quantize_channel_kernel(const Quant
 
 template <int BITS, int G, bool ASYM>
 void launch_q_heads(const QuantArgs& a, int mode, int64_t L, hipStream_t st) {
-  const unsigned n_groups = static_cast<unsigned>(ceil_div(a.rows_per_layer / a.H, G));
-  // heads per block: 8 when the plane has that many, so that a load step is one contiguous run;
-  // 4 for groups of 128 slots, which keeps a thread at 8 rows (16 would spill registers)
-  if (a.H >= 8 && G <= 64) {
-    quantize_channel_kernel<BITS, G, 8, ASYM><<<dim3(n_groups, (a.H + 7) / 8, L), kThreadsQ, 0, st>>>(a, mode);
-  } else if (a.H >= 4) {
-    quantize_channel_kernel<BITS, G, 4, ASYM><<<dim3(n_groups, (a.H + 3) / 4, L), kThreadsQ, 0, st>>>(a, mode);
-  } else {
-    quantize_channel_kernel<BITS, G, 2, ASYM><<<dim3(n_groups, (a.H + 1) / 2, L), kThreadsQ, 0, st>>>(a, mode);
-  }
+  constexpr int HB = shape_for(G).heads, kThreadsQ = shape_for(G).threads;
+  const uint32_t n_groups = static_cast<uint32_t>(ceil_div(a.rows_per_layer / a.H, G));
+  const uint32_t n_tiles = (a.H + HB - 1) / HB;
+  quantize_channel_kernel<BITS, G, HB, kThreadsQ, ASYM><<<dim3(n_groups * n_tiles, static_cast<unsigned>(L)), kThreadsQ, 0, st>>>(
+      a, mode, n_groups, n_tiles, FastDiv(n_tiles));
 }
 
 template <int BITS, bool ASYM>
