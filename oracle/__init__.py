@@ -63,6 +63,8 @@ def lib():
         _lib.oracle_dequantize_paged_channel.restype = ctypes.c_int
         _lib.oracle_dequantize_paged_channel.argtypes = [_p, _p, _p, ctypes.c_int, ctypes.c_int, ctypes.c_int, _i64, _i64,
                                                          _i64, _i64, _i64, _p, _i64, _i64, _p, _i64]
+        _lib.oracle_smooth_scores.restype = ctypes.c_int
+        _lib.oracle_smooth_scores.argtypes = [_p, _i64, _i64, _i64, _i64, ctypes.c_int, ctypes.c_int, _p, _i64]
         _lib.oracle_score_tokens.restype = ctypes.c_int
         _lib.oracle_score_tokens.argtypes = [_p, _i64, _i64, _i64, _i64, _i64, _p, _i64, _i64, _i64, _i64,
                                              _i64, _i64, _i64, ctypes.c_int, ctypes.c_int, _p]
@@ -274,6 +276,17 @@ def score_keys(k: np.ndarray, method: int, tokens: np.ndarray | None = None) -> 
     out = np.empty((L, H, n if tokens is not None else T), dtype=np.float32)
     _check(lib().oracle_score_keys(_ptr(k), L, T, H, D, ksl, kst, ksh, int(method), _ptr(tokens), n, _ptr(out)),
            "score_keys")
+    return out
+
+
+def smooth_scores(scores: np.ndarray, window: int, kernel: int, mode: str = "avg") -> np.ndarray:
+    """1-D pooling of the prefix scores along tokens (window positions copied): f32 [n_rows][T] -> same."""
+    assert scores.dtype == np.float32 and scores.ndim == 2 and scores.strides[1] == 4
+    n_rows, T = scores.shape
+    row_stride = scores.strides[0] // 4 if n_rows > 1 else T
+    out = np.full((n_rows, T), np.nan, dtype=np.float32)
+    _check(lib().oracle_smooth_scores(_ptr(scores), n_rows, T, row_stride, window, kernel,
+                                      {"avg": 0, "max": 1}[mode], _ptr(out), T), "smooth_scores")
     return out
 
 

@@ -526,6 +526,39 @@ int oracle_score_tokens(const uint16_t* q, int64_t W, int64_t Hq, int64_t q_sl, 
   return 0;
 }
 
+// Score smoothing before the selection (the published snapkv method that the paper's Baselines
+// evaluate pools the summed attention votes along the token axis, so that neighbours of an
+// important token are kept with it).  For the prefix positions t < T - window:
+//   mode 0 (average): out[t] = (sum of scores[u], |u - t| <= kernel/2, 0 <= u < T - window) / kernel
+//                     (positions outside the prefix count as zeros: the divisor is always `kernel`)
+//   mode 1 (maximum): out[t] = max of the same in-range scores
+// The last `window` positions (the observation window, kept unconditionally) are copied unchanged
+// and never leak into the prefix.  kernel is odd.  Sums are formed in double.
+int oracle_smooth_scores(const float* scores, int64_t n_rows, int64_t T, int64_t row_stride, int64_t window,
+                         int kernel, int mode, float* out, int64_t out_stride) {
+  if (!scores || !out || n_rows < 0 || T <= 0 || window < 0 || window > T) return -1;
+  if (kernel < 1 || kernel % 2 == 0 || (mode != 0 && mode != 1)) return -1;
+  const int64_t P = T - window, r = kernel / 2;
+  for (int64_t row = 0; row < n_rows; ++row) {
+    const float* in = scores + row * row_stride;
+    float* o = out + row * out_stride;
+    for (int64_t t = 0; t < P; ++t) {
+      const int64_t u0 = std::max<int64_t>(0, t - r), u1 = std::min<int64_t>(P - 1, t + r);
+      if (mode == 0) {
+        double sum = 0.0;
+        for (int64_t u = u0; u <= u1; ++u) sum += static_cast<double>(in[u]);
+        o[t] = static_cast<float>(sum / static_cast<double>(kernel));
+      } else {
+        float m = in[u0];
+        for (int64_t u = u0 + 1; u <= u1; ++u) m = std::max(m, in[u]);
+        o[t] = m;
+      }
+    }
+    for (int64_t t = P; t < T; ++t) o[t] = in[t];
+  }
+  return 0;
+}
+
 // Per-row top-k keep-set: indices of the k largest scores of each row, ties
 // toward the lowest index, written ascending.  scores is n_rows rows of T
 // floats, row_stride floats apart; idx_out is [n_rows][k] int32.
