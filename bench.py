@@ -333,6 +333,8 @@ def side_measurements(kvp, workloads, torch, dev, K8, V8):
     qk = kvp.alloc_qplane(Ls, k, c["H"], c["D"], c["bits"], c["group"], dev)
     t_score = _time_loop(torch, lambda: kvp.kvp_score_tokens(Qc, Kc, sc, ws=ws), 5)
     t_sel = _time_loop(torch, lambda: kvp.kvp_select_topk(sc.view(Ls * c["H"], c["T"]), k, idx), 10)
+    sm = torch.empty(Ls * c["H"], c["T"], dtype=torch.float32, device=dev)
+    t_smooth = _time_loop(torch, lambda: kvp.kvp_smooth_scores(sc.view(Ls * c["H"], c["T"]), c["W"], 7, "max", out=sm), 10)
     keep = idx.view(Ls, c["H"], k)
     t_gq = _time_loop(torch, lambda: kvp.kvp_quantize(Kc, qk, keep_idx=keep), 5)
     M = c["G"] * c["W"]
@@ -345,9 +347,10 @@ def side_measurements(kvp, workloads, torch, dev, K8, V8):
         "score_frac_mfma": round(flops / t_score / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
         "select_us": round(t_sel * 1e6, 1), "select_GBs_alg": round(sel_bytes / t_sel / 1e9, 1),
         "select_frac_hbm": round(sel_bytes / t_sel / 1e9 / HBM_PEAK_GBS, 4),
+        "smooth_k7_us": round(t_smooth * 1e6, 1), "smooth_GBs_alg": round(2 * sc.numel() * 4 / t_smooth / 1e9, 1),
         "gather_quantize_ms_per_plane": round(t_gq * 1e3, 3), "gather_quantize_GBs_alg": round(gq_bytes / t_gq / 1e9, 1),
         "pipeline_input_GBs": round(2 * Kc.numel() * 2 / (t_score + t_sel + 2 * t_gq) / 1e9, 1)}
-    del Kc, Vc, Qc, sc, ws, idx, qk
+    del Kc, Vc, Qc, sc, sm, ws, idx, qk
     # --- long-context select: 112 rows of 131072 scores ---
     c = workloads.CONFIGS["long_context_int2"]
     rows = c["L"] * c["H"]

@@ -162,6 +162,19 @@ int32_t kvp_select_topk(const float* scores, int64_t n_rows, int64_t T, int64_t 
                         int32_t* idx_out, void* ws, size_t ws_bytes, void* stream);
 size_t kvp_select_workspace_bytes(int64_t n_rows, int64_t T, int64_t k);
 
+/* Score smoothing before the selection (Evaluation, Baselines: snapkv; the published method pools
+ * the summed attention votes along the token axis so that the neighbours of an important token are
+ * kept with it).  Rows as in kvp_select_topk; P = T - window is the prefix length.  For t < P:
+ *     KVP_SMOOTH_AVG: out[t] = (sum of scores[u], |u - t| <= kernel/2, 0 <= u < P) / kernel
+ *                     (taps outside the prefix count as zeros; fp32 sum, left to right)
+ *     KVP_SMOOTH_MAX: out[t] = max of the same in-range scores
+ * and out[t] = scores[t] for the `window` last positions, which never enter a prefix tap (with
+ * kvp_score_tokens(force_window=1) they hold +inf).  kernel is odd, 1 <= kernel <= 63;
+ * 0 <= window <= T; out (device fp32, rows out_stride floats apart) must not overlap scores. */
+enum { KVP_SMOOTH_AVG = 0, KVP_SMOOTH_MAX = 1 };
+int32_t kvp_smooth_scores(const float* scores, int64_t n_rows, int64_t T, int64_t row_stride, int64_t window,
+                          int32_t kernel, int32_t mode, float* out, int64_t out_stride, void* stream);
+
 /* Quality-loss proxy for every candidate configuration of ONE context
  * (System design, profiler module: the KV cache is compressed "with different
  * methods and ratios" and every version is scored; utility function: the

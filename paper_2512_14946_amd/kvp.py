@@ -74,6 +74,8 @@ def _load(path: str = _LIB_PATH):
     lib.kvp_score_keys.argtypes = [P(_View), _i32, _vp, _vp, _sz, _vp]
     lib.kvp_score_keys_workspace_bytes.restype = _sz
     lib.kvp_score_keys_workspace_bytes.argtypes = [_i64, _i64, _i64, _i32]
+    lib.kvp_smooth_scores.restype = _i32
+    lib.kvp_smooth_scores.argtypes = [_vp, _i64, _i64, _i64, _i64, _i32, _i32, _vp, _i64, _vp]
     lib.kvp_select_topk.restype = _i32
     lib.kvp_select_topk.argtypes = [_vp, _i64, _i64, _i64, _i64, _vp, _vp, _sz, _vp]
     lib.kvp_select_workspace_bytes.restype = _sz
@@ -323,6 +325,23 @@ def kvp_select_topk(scores: torch.Tensor, k: int, idx_out: torch.Tensor | None =
     _check(_lib.kvp_select_topk(scores.data_ptr(), n_rows, T, row_stride, k, idx_out.data_ptr(), wp, wb,
                                 _stream(stream)), "kvp_select_topk")
     return idx_out
+
+
+def kvp_smooth_scores(scores: torch.Tensor, window: int, kernel: int, mode: str = "avg",
+                      out: torch.Tensor | None = None, stream=None) -> torch.Tensor:
+    """1-D pooling ("avg" or "max", odd kernel) of the prefix scores of f32 [n_rows][T]; window entries copied."""
+    _need_cuda(scores, out)
+    if scores.dtype != torch.float32 or scores.dim() != 2 or (scores.shape[1] > 1 and scores.stride(1) != 1):
+        raise ValueError("scores must be float32 [n_rows][T] with contiguous rows")
+    n_rows, T = scores.shape
+    if out is None:
+        out = torch.empty(n_rows, T, dtype=torch.float32, device=scores.device)
+    if out.dtype != torch.float32 or tuple(out.shape) != (n_rows, T) or (T > 1 and out.stride(1) != 1):
+        raise ValueError("out must be float32 [n_rows][T] with contiguous rows")
+    _check(_lib.kvp_smooth_scores(scores.data_ptr(), n_rows, T, scores.stride(0) if n_rows > 1 else T, window, kernel,
+                                  {"avg": 0, "max": 1}[mode], out.data_ptr(), out.stride(0) if n_rows > 1 else T,
+                                  _stream(stream)), "kvp_smooth_scores")
+    return out
 
 
 def kvp_eval_workspace_bytes(L: int, Hkv: int, Hq: int, W: int, T: int, n_cfgs: int) -> int:

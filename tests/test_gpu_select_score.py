@@ -130,3 +130,47 @@ def test_score_then_select_overlap():
     ref_idx = oracle.select_topk(oracle.score_tokens(torch_bits(Q), torch_bits(K)).reshape(L * H, T), k)
     overlap = np.mean([len(set(a) & set(b)) / k for a, b in zip(idx.cpu().numpy(), ref_idx)])
     assert overlap > 0.99
+
+
+@pytest.mark.parametrize("T,window,kernel", [(203, 0, 1), (4096, 32, 7), (5003, 64, 13), (16384, 64, 5), (2049, 5, 63),
+                                             (40, 40, 3), (70, 69, 7)])
+def test_smooth_scores_match_oracle(T, window, kernel):
+    kvp = _kvp()
+    _say("smooth", T, window, kernel)
+    rows = 6
+    big = workloads.make_scores(rows, T + 9, seed=T + kernel, device="cpu")
+    s = big[:, :T]                                                  # strided rows
+    s[:, T - window:] = float("inf")
+    sg = big.to(DEV)[:, :T]
+    s_np = s.numpy()
+    for mode in ("avg", "max"):
+        got = kvp.kvp_smooth_scores(sg, window, kernel, mode)
+        torch.cuda.synchronize()
+        ref = oracle.smooth_scores(s_np, window, kernel, mode)
+        g = got.cpu().numpy()
+        P = T - window
+        assert np.array_equal(g[:, P:], ref[:, P:])
+        if mode == "max":
+            assert np.array_equal(g, ref)
+        else:   # fp32 left-to-right sum of <= 63 non-negative terms against a double sum
+            assert np.all(np.abs(g[:, :P] - ref[:, :P]) <= 1e-5 * np.abs(ref[:, :P]) + 1e-30)
+        # the pipeline the method runs: smooth, then select; selection is exact on the GPU's own rows
+        k = max(1, min(T, window + (T - window) // 3))
+        idx = kvp.kvp_select_topk(got, k)
+        torch.cuda.synchronize()
+        assert np.array_equal(idx.cpu().numpy(), oracle.select_topk(g, k))
+
+
+def test_smooth_scores_errors():
+    kvp = _kvp()
+    _say("smooth errors")
+    s = torch.zeros(2, 64, device=DEV)
+    for bad_kernel in (0, 4, 65):
+        with pytest.raises(kvp.KVPError) as e:
+            kvp.kvp_smooth_scores(s, 4, bad_kernel)
+        assert e.value.code == -4
+    with pytest.raises(kvp.KVPError):
+        kvp.kvp_smooth_scores(s, 65, 3)                              # window longer than the row
+    with pytest.raises(kvp.KVPError):
+        kvp.kvp_smooth_scores(s, 4, 3, out=s)                        # in place
+    torch.cuda.synchronize()
