@@ -63,6 +63,9 @@ def lib():
         _lib.oracle_dequantize_paged_channel.restype = ctypes.c_int
         _lib.oracle_dequantize_paged_channel.argtypes = [_p, _p, _p, ctypes.c_int, ctypes.c_int, ctypes.c_int, _i64, _i64,
                                                          _i64, _i64, _i64, _p, _i64, _i64, _p, _i64]
+        _lib.oracle_dequantize_paged_scatter.restype = ctypes.c_int
+        _lib.oracle_dequantize_paged_scatter.argtypes = [_p, _p, _p, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+                                                         _i64, _i64, _i64, _i64, _i64, _p, _i64, _p, _i64, _i64, _p, _i64]
         _lib.oracle_smooth_scores.restype = ctypes.c_int
         _lib.oracle_smooth_scores.argtypes = [_p, _i64, _i64, _i64, _i64, ctypes.c_int, ctypes.c_int, _p, _i64]
         _lib.oracle_score_tokens.restype = ctypes.c_int
@@ -277,6 +280,28 @@ def score_keys(k: np.ndarray, method: int, tokens: np.ndarray | None = None) -> 
     _check(lib().oracle_score_keys(_ptr(k), L, T, H, D, ksl, kst, ksh, int(method), _ptr(tokens), n, _ptr(out)),
            "score_keys")
     return out
+
+
+def dequantize_paged_scatter(codes, scales, mins, bits: int, group: int, keep_idx, T: int, block_table,
+                             num_blocks: int, bs: int, pool: np.ndarray | None = None, fill: int = 0x7FC0,
+                             per_channel: bool = False):
+    """Restore the k slots of a dropped+quantized plane at their original token positions of a T-token pool."""
+    codes = np.ascontiguousarray(codes)
+    scales = np.ascontiguousarray(scales, dtype=np.float32)
+    if mins is not None:
+        mins = np.ascontiguousarray(mins, dtype=np.float32)
+    keep_idx = np.ascontiguousarray(keep_idx, dtype=np.int32)
+    L, Tp, H, cb = codes.shape
+    D = cb * 8 // bits
+    k = keep_idx.shape[2]
+    block_table = np.ascontiguousarray(block_table, dtype=np.int32)
+    if pool is None:
+        pool = np.full((L, num_blocks, bs, H, D), fill, dtype=np.uint16)
+    _check(lib().oracle_dequantize_paged_scatter(_ptr(codes), _ptr(scales), _ptr(mins), bits, group, int(mins is not None),
+                                                 int(per_channel), L, k, Tp, H, D, _ptr(keep_idx), T, _ptr(block_table),
+                                                 num_blocks, bs, _ptr(pool), num_blocks * bs * H * D),
+           "dequantize_paged_scatter")
+    return pool
 
 
 def smooth_scores(scores: np.ndarray, window: int, kernel: int, mode: str = "avg") -> np.ndarray:

@@ -526,6 +526,47 @@ int oracle_score_tokens(const uint16_t* q, int64_t W, int64_t Hq, int64_t q_sl, 
   return 0;
 }
 
+// Restore of a dropped-and-quantized plane at the ORIGINAL token positions: slot i of head h of a
+// compressed plane with k slots came from token keep_idx[l][h][i] (see oracle_quantize with a keep
+// list) and is written back to that token's place in a paged pool that spans all T tokens,
+//   pool[l][block_table[t / bs]][t % bs][h][:] = dequantized slot i,  t = keep_idx[l][h][i];
+// positions of dropped tokens are left untouched.  Any of the four codecs: asym (unsigned codes plus
+// minimum) or not, group_axis 0 (groups of channels, scales [L][Tp][H][D/group]) or 1 (groups of
+// token slots, scales [L][ceil(Tp/group)][H][D]).  One binary32 multiply (and one add), bf16 RNE.
+int oracle_dequantize_paged_scatter(const uint8_t* codes, const float* scales, const float* mins, int bits, int group,
+                                    int asym, int group_axis, int64_t L, int64_t k, int64_t Tp, int64_t H, int64_t D,
+                                    const int32_t* keep_idx, int64_t T, const int32_t* block_table,
+                                    int64_t num_blocks, int64_t bs, uint16_t* pool, int64_t pool_stride_l) {
+  if (!codes || !scales || (asym && !mins) || !keep_idx || !block_table || !pool) return -1;
+  if ((bits != 8 && bits != 4 && bits != 2) || group <= 0 || D <= 0 || (D * bits) % 8 != 0) return -1;
+  if (group_axis == 0 && D % group != 0) return -1;
+  if (k < 0 || k > Tp || k > T || bs <= 0) return -1;
+  const int64_t cb = D * bits / 8;
+  const int per_byte = 8 / bits;
+  const uint32_t field_mask = (1u << bits) - 1u;
+  const int sign_bit = 1 << (bits - 1);
+  const int64_t n_groups = (Tp + group - 1) / group;
+  for (int64_t l = 0; l < L; ++l)
+    for (int64_t h = 0; h < H; ++h)
+      for (int64_t i = 0; i < k; ++i) {
+        const int64_t t = keep_idx[(l * H + h) * k + i];
+        if (t < 0 || t >= T) return -1;
+        const int64_t blk = block_table[t / bs];
+        if (blk < 0 || blk >= num_blocks) return -1;
+        for (int64_t c = 0; c < D; ++c) {
+          const uint8_t byte = codes[((l * Tp + i) * H + h) * cb + c / per_byte];
+          int q = static_cast<int>((byte >> (bits * (c % per_byte))) & field_mask);
+          if (!asym && (q & sign_bit)) q -= (1 << bits);
+          const int64_t so = group_axis == 0 ? ((l * Tp + i) * H + h) * (D / group) + c / group
+                                             : ((l * n_groups + i / group) * H + h) * D + c;
+          float y = static_cast<float>(q) * scales[so];
+          if (asym) y = y + mins[so];
+          pool[l * pool_stride_l + ((blk * bs + t % bs) * H + h) * D + c] = f32_to_bf16_rne(y);
+        }
+      }
+  return 0;
+}
+
 // Score smoothing before the selection (the published snapkv method that the paper's Baselines
 // evaluate pools the summed attention votes along the token axis, so that neighbours of an
 // important token are kept with it).  For the prefix positions t < T - window:
