@@ -126,6 +126,16 @@ int32_t kvp_quantize(const kvp_view* src, const kvp_paged* src_paged, const int3
  * page lies inside one group (KVP_ERR_UNSUPPORTED otherwise). */
 int32_t kvp_dequantize_paged(const kvp_qplane* src, const kvp_paged* dst, void* stream);
 
+/* Restore of a dropped-and-quantized plane at the ORIGINAL token positions (Limitations: the pool
+ * "that combines both token dropping and quantization"; Implementation: retrieve into paged GPU
+ * memory).  src holds k = src->T slots per head, written by kvp_quantize with the same keep_idx
+ * (device int32 [L][H][k], values in [0, dst->T)); slot i of head h is dequantized as in
+ * kvp_dequantize_paged and stored at token t = keep_idx[l][h][i] of the pool, which spans
+ * dst->T >= k tokens:  pool[l][block_table[t/bs]][t%bs][h][:].  Rows of dropped tokens are not
+ * written.  keep_idx doubles as the position ids of the restored rows. */
+int32_t kvp_dequantize_paged_scatter(const kvp_qplane* src, const int32_t* keep_idx, const kvp_paged* dst,
+                                     void* stream);
+
 /* Attention-score token importance (Evaluation, Baselines: snapkv "computes
  * the cross attention between tokens near the query and the earlier
  * contexts").  q_win is [L][W][Hq][D]: the queries of the last W positions

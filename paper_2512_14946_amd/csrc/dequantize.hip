@@ -21,7 +21,7 @@ constexpr int kThreads = 256;
 constexpr int kRowsPerStep = kThreads / kLanesPerRow;  // 16
 constexpr int kUnroll = 8;                             // a 16-token x 8-head page in one sweep
 
-template <int BITS, int GROUP, bool ASYM>
+template <int BITS, int GROUP, bool ASYM, bool SCATTER>
 __global__ __launch_bounds__(kThreads) void dequantize_paged_kernel(const DequantArgs a) {
   constexpr int CB = kHeadDim * BITS / 8;
   constexpr int NS = kHeadDim / GROUP;
@@ -34,7 +34,7 @@ __global__ __launch_bounds__(kThreads) void dequantize_paged_kernel(const Dequan
   const uint32_t tokens = min(a.bs, a.T - t0);
   const uint32_t rows = tokens * a.H;  // rows of this page that hold tokens < T
   // an out-of-contract table entry is clamped so that it cannot fault the GPU
-  const int64_t blk = min(static_cast<uint32_t>(a.block_table[page]), a.num_blocks - 1);
+  const int64_t blk = SCATTER ? 0 : min(static_cast<uint32_t>(a.block_table[page]), a.num_blocks - 1);
   const int64_t src_row0 = (static_cast<int64_t>(l) * a.Tp + t0) * a.H;
   const uint8_t* codes = a.codes + src_row0 * CB;
   const float* scales = a.scales + src_row0 * NS;
@@ -71,18 +71,27 @@ __global__ __launch_bounds__(kThreads) void dequantize_paged_kernel(const Dequan
         }
         w[i] = pack_bf16x2(lo, hi);
       }
-      store_stream16(dst + static_cast<int64_t>(r) * kHeadDim + lane_in_row * 8, make_uint4(w[0], w[1], w[2], w[3]));
+      uint16_t* out_row = SCATTER ? scatter_row(a, l, t0, r) : dst + static_cast<int64_t>(r) * kHeadDim;
+      store_stream16(out_row + lane_in_row * 8, make_uint4(w[0], w[1], w[2], w[3]));
     }
+  }
+}
+
+template <int BITS, bool ASYM, bool SCATTER>
+void launch_group3(int group, dim3 grid, hipStream_t st, const DequantArgs& a) {
+  switch (group) {
+    case 32: dequantize_paged_kernel<BITS, 32, ASYM, SCATTER><<<grid, kThreads, 0, st>>>(a); break;
+    case 64: dequantize_paged_kernel<BITS, 64, ASYM, SCATTER><<<grid, kThreads, 0, st>>>(a); break;
+    default: dequantize_paged_kernel<BITS, 128, ASYM, SCATTER><<<grid, kThreads, 0, st>>>(a); break;
   }
 }
 
 template <int BITS, bool ASYM>
 void launch_group2(int group, dim3 grid, hipStream_t st, const DequantArgs& a) {
-  switch (group) {
-    case 32: dequantize_paged_kernel<BITS, 32, ASYM><<<grid, kThreads, 0, st>>>(a); break;
-    case 64: dequantize_paged_kernel<BITS, 64, ASYM><<<grid, kThreads, 0, st>>>(a); break;
-    default: dequantize_paged_kernel<BITS, 128, ASYM><<<grid, kThreads, 0, st>>>(a); break;
-  }
+  if (a.keep_idx)
+    launch_group3<BITS, ASYM, true>(group, grid, st, a);
+  else
+    launch_group3<BITS, ASYM, false>(group, grid, st, a);
 }
 
 template <int BITS>
@@ -102,13 +111,18 @@ __global__ __launch_bounds__(256) void copy_kernel(uint4* __restrict__ dst, cons
 }  // namespace
 }  // namespace kvp
 
-extern "C" int32_t kvp_dequantize_paged(const kvp_qplane* src, const kvp_paged* dst, void* stream) {
-  using namespace kvp;
+namespace kvp {
+namespace {
+
+// Common body of kvp_dequantize_paged (keep_idx == nullptr) and kvp_dequantize_paged_scatter.
+int32_t dequantize_impl(const kvp_qplane* src, const int32_t* keep_idx, const kvp_paged* dst, void* stream) {
   int32_t rc = check_qplane(src);
   if (rc != KVP_OK) return rc;
   rc = check_paged(dst);
   if (rc != KVP_OK) return rc;
-  if (src->L != dst->L || src->H != dst->H || src->T != dst->T) return KVP_ERR_SHAPE;
+  if (src->L != dst->L || src->H != dst->H) return KVP_ERR_SHAPE;
+  if (keep_idx ? src->T > dst->T : src->T != dst->T) return KVP_ERR_SHAPE;
+  if (keep_idx && (reinterpret_cast<uintptr_t>(keep_idx) & 3u)) return KVP_ERR_ALIGN;
   if (dst->T >= (1ll << 31) || dst->bs * dst->H >= (1ll << 31) || dst->num_blocks >= (1ll << 31) || dst->L > 65535)
     return KVP_ERR_SHAPE;
   DequantArgs a{};
@@ -119,11 +133,16 @@ extern "C" int32_t kvp_dequantize_paged(const kvp_qplane* src, const kvp_paged* 
   a.block_table = dst->block_table;
   a.pool_stride_l = dst->stride_l;
   a.Tp = src->Tp;
-  a.T = static_cast<uint32_t>(dst->T);
+  a.T = static_cast<uint32_t>(src->T);
   a.H = static_cast<uint32_t>(dst->H);
   a.bs = static_cast<uint32_t>(dst->bs);
   a.num_blocks = static_cast<uint32_t>(dst->num_blocks);
-  const dim3 grid(static_cast<unsigned>(ceil_div(dst->T, dst->bs)), static_cast<unsigned>(dst->L));
+  a.keep_idx = keep_idx;
+  a.k = src->T;
+  a.T_full = static_cast<uint32_t>(dst->T);
+  a.div_h = FastDiv(a.H);
+  a.div_bs = FastDiv(a.bs);
+  const dim3 grid(static_cast<unsigned>(ceil_div(src->T, dst->bs)), static_cast<unsigned>(dst->L));
   const hipStream_t st = as_stream(stream);
   if (src->group_axis == KVP_GROUP_TOKENS) {
     if (src->group % dst->bs != 0) return KVP_ERR_UNSUPPORTED;
@@ -136,6 +155,19 @@ extern "C" int32_t kvp_dequantize_paged(const kvp_qplane* src, const kvp_paged* 
     default: launch_group<2>(src->group, grid, st, a); break;
   }
   return launch_status();
+}
+
+}  // namespace
+}  // namespace kvp
+
+extern "C" int32_t kvp_dequantize_paged(const kvp_qplane* src, const kvp_paged* dst, void* stream) {
+  return kvp::dequantize_impl(src, nullptr, dst, stream);
+}
+
+extern "C" int32_t kvp_dequantize_paged_scatter(const kvp_qplane* src, const int32_t* keep_idx, const kvp_paged* dst,
+                                                void* stream) {
+  if (!keep_idx) return KVP_ERR_NULL;
+  return kvp::dequantize_impl(src, keep_idx, dst, stream);
 }
 
 extern "C" int32_t kvp_copy_bytes(void* dst, const void* src, size_t nbytes, void* stream) {

@@ -41,11 +41,26 @@ struct DequantArgs {
   const int32_t* block_table;
   int64_t pool_stride_l;   // elements
   int64_t Tp;
-  uint32_t T, H, bs, num_blocks;
+  uint32_t T, H, bs, num_blocks;   // T: slots of the compressed plane to restore
+  // scatter restore only: slot i of head h goes to token keep_idx[l][h][i] of a pool that spans T_full tokens
+  const int32_t* keep_idx;
+  int64_t k;
+  uint32_t T_full;
+  FastDiv div_h, div_bs;
 };
+
+// Destination row of the scatter restore: source row r of a block whose first slot is t0.
+__device__ __forceinline__ uint16_t* scatter_row(const DequantArgs& a, uint32_t l, uint32_t t0, uint32_t r) {
+  const uint32_t di = a.div_h.quot(r), h = r - di * a.H;
+  // an out-of-contract index is clamped so that a bad keep list cannot fault the GPU
+  const uint32_t t = min(static_cast<uint32_t>(a.keep_idx[(static_cast<int64_t>(l) * a.H + h) * a.k + t0 + di]), a.T_full - 1);
+  const uint32_t pg = a.div_bs.quot(t);
+  const int64_t blk = min(static_cast<uint32_t>(a.block_table[pg]), a.num_blocks - 1);
+  return a.pool + static_cast<int64_t>(l) * a.pool_stride_l + ((blk * a.bs + (t - pg * a.bs)) * a.H + h) * kHeadDim;
+}
 
 // Groups along the token axis (KVP_GROUP_TOKENS): kernel launches for validated arguments.
 void quantize_channel_launch(const QuantArgs& a, int bits, int group, int mode, int64_t L, hipStream_t st);
-void dequantize_channel_launch(const DequantArgs& a, int bits, int group, int64_t L, hipStream_t st);
+void dequantize_channel_launch(const DequantArgs& a, int bits, int group, int64_t L, hipStream_t st);  // scatter if a.keep_idx
 
 }  // namespace kvp

@@ -290,7 +290,7 @@ constexpr int kThreadsD = 256;
 constexpr int kRowsPerStepD = kThreadsD / kLanesPerRow;  // 16
 constexpr int kUnrollD = 8;
 
-template <int BITS, bool ASYM>
+template <int BITS, bool ASYM, bool SCATTER>
 __global__ __launch_bounds__(kThreadsD) void dequantize_channel_kernel(const DequantArgs a, const uint32_t group,
                                                                        const uint32_t n_groups, const FastDiv div_h) {
   constexpr int CB = kHeadDim * BITS / 8;
@@ -299,7 +299,7 @@ __global__ __launch_bounds__(kThreadsD) void dequantize_channel_kernel(const Deq
   const uint32_t page = blockIdx.x, l = blockIdx.y;
   const uint32_t t0 = page * a.bs;
   const uint32_t rows = min(a.bs, a.T - t0) * a.H;
-  const int64_t blk = min(static_cast<uint32_t>(a.block_table[page]), a.num_blocks - 1);
+  const int64_t blk = SCATTER ? 0 : min(static_cast<uint32_t>(a.block_table[page]), a.num_blocks - 1);
   const uint8_t* codes = a.codes + (static_cast<int64_t>(l) * a.Tp + t0) * a.H * CB;
   const int64_t group_row0 = (static_cast<int64_t>(l) * n_groups + t0 / group) * a.H;   // the page's group
   uint16_t* dst = a.pool + static_cast<int64_t>(l) * a.pool_stride_l + blk * a.bs * a.H * kHeadDim;
@@ -343,7 +343,8 @@ __global__ __launch_bounds__(kThreadsD) void dequantize_channel_kernel(const Deq
         }
         w[i] = pack_bf16x2(y0, y1);
       }
-      store_stream16(dst + static_cast<int64_t>(r) * kHeadDim + lane16 * 8, make_uint4(w[0], w[1], w[2], w[3]));
+      uint16_t* out_row = SCATTER ? scatter_row(a, l, t0, r) : dst + static_cast<int64_t>(r) * kHeadDim;
+      store_stream16(out_row + lane16 * 8, make_uint4(w[0], w[1], w[2], w[3]));
     }
   }
 }
@@ -352,10 +353,18 @@ template <int BITS>
 void launch_d_bits(const DequantArgs& a, int group, int64_t L, hipStream_t st) {
   const dim3 grid(static_cast<unsigned>(ceil_div(a.T, a.bs)), static_cast<unsigned>(L));
   const uint32_t n_groups = static_cast<uint32_t>(ceil_div(a.Tp, group));
-  if (a.mins)
-    dequantize_channel_kernel<BITS, true><<<grid, kThreadsD, 0, st>>>(a, group, n_groups, FastDiv(a.H));
-  else
-    dequantize_channel_kernel<BITS, false><<<grid, kThreadsD, 0, st>>>(a, group, n_groups, FastDiv(a.H));
+  const FastDiv dh(a.H);
+  if (a.mins) {
+    if (a.keep_idx)
+      dequantize_channel_kernel<BITS, true, true><<<grid, kThreadsD, 0, st>>>(a, group, n_groups, dh);
+    else
+      dequantize_channel_kernel<BITS, true, false><<<grid, kThreadsD, 0, st>>>(a, group, n_groups, dh);
+  } else {
+    if (a.keep_idx)
+      dequantize_channel_kernel<BITS, false, true><<<grid, kThreadsD, 0, st>>>(a, group, n_groups, dh);
+    else
+      dequantize_channel_kernel<BITS, false, false><<<grid, kThreadsD, 0, st>>>(a, group, n_groups, dh);
+  }
 }
 
 }  // namespace

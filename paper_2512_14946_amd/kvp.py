@@ -66,6 +66,8 @@ def _load(path: str = _LIB_PATH):
     lib.kvp_quantize.argtypes = [P(_View), P(_Paged), _vp, _i64, P(_QPlane), _vp]
     lib.kvp_dequantize_paged.restype = _i32
     lib.kvp_dequantize_paged.argtypes = [P(_QPlane), P(_Paged), _vp]
+    lib.kvp_dequantize_paged_scatter.restype = _i32
+    lib.kvp_dequantize_paged_scatter.argtypes = [P(_QPlane), _vp, P(_Paged), _vp]
     lib.kvp_score_tokens.restype = _i32
     lib.kvp_score_tokens.argtypes = [P(_View), P(_View), _i32, _i32, _vp, _vp, _sz, _vp]
     lib.kvp_score_workspace_bytes.restype = _sz
@@ -258,6 +260,17 @@ def kvp_dequantize_paged(src: QPlane, dst: PagedKV, stream=None) -> PagedKV:
     _need_cuda(src.codes, src.scales, src.mins, dst.pool, dst.block_table)
     qp, pg = _qplane(src), _paged(dst)
     _check(_lib.kvp_dequantize_paged(ctypes.byref(qp), ctypes.byref(pg), _stream(stream)), "kvp_dequantize_paged")
+    return dst
+
+
+def kvp_dequantize_paged_scatter(src: QPlane, keep_idx: torch.Tensor, dst: PagedKV, stream=None) -> PagedKV:
+    """Restore the k slots of a dropped+quantized plane at tokens keep_idx int32 [L][H][k] of a T-token pool."""
+    _need_cuda(src.codes, src.scales, src.mins, keep_idx, dst.pool, dst.block_table)
+    qp, pg = _qplane(src), _paged(dst)
+    if keep_idx.dtype != torch.int32 or not keep_idx.is_contiguous() or tuple(keep_idx.shape) != (qp.L, qp.H, src.T):
+        raise ValueError("keep_idx must be contiguous int32 [L][H][k] with k = src.T")
+    _check(_lib.kvp_dequantize_paged_scatter(ctypes.byref(qp), keep_idx.data_ptr(), ctypes.byref(pg), _stream(stream)),
+           "kvp_dequantize_paged_scatter")
     return dst
 
 

@@ -127,3 +127,59 @@ def test_channel_argument_errors():
     with pytest.raises((kvp.KVPError, ValueError)):
         kvp.kvp_quantize(x, bad)
     torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("bits,group,asym,per_channel,H", [(4, 64, False, False, 8), (2, 32, True, False, 3),
+                                                           (8, 128, False, True, 8), (4, 32, True, True, 5),
+                                                           (8, 32, True, False, 12), (2, 64, False, True, 4)])
+def test_scatter_restore_to_original_positions(bits, group, asym, per_channel, H):
+    kvp = _kvp()
+    L, T, D, bs, k = 2, 333, 128, 16, 141
+    _say("scatter restore", bits, group, asym, per_channel, H)
+    K, _ = workloads.make_kv(L, T, H, D, seed=31 + H)
+    xb = torch_bits(K)
+    x = K.to(DEV)
+    rng = np.random.default_rng(H)
+    keep = np.stack([[np.sort(rng.choice(T, k, replace=False)) for _ in range(H)] for _ in range(L)]).astype(np.int32)
+    keep_g = torch.from_numpy(keep).to(DEV)
+    qp = kvp.alloc_qplane(L, k, H, D, bits, group, DEV, asymmetric=asym, per_channel=per_channel)
+    kvp.kvp_quantize(x, qp, keep_idx=keep_g)
+    bt, nb = workloads.make_block_table(T, bs, seed=8, spare=2, device=DEV)
+    before = rng.integers(0, 0x7F80, (L, nb, bs, H, D)).astype(np.uint16)
+    pool = bits_to_torch(before, DEV)
+    pg = kvp.PagedKV(pool, bt, T)
+    kvp.kvp_dequantize_paged_scatter(qp, keep_g, pg)
+    torch.cuda.synchronize()
+    codes, scales = qp.codes.cpu().numpy(), qp.scales.cpu().numpy()
+    mins = qp.mins.cpu().numpy() if asym else None
+    want = oracle.dequantize_paged_scatter(codes, scales, mins, bits, group, keep, T, bt.cpu().numpy(), nb, bs,
+                                           pool=before.copy(), per_channel=per_channel)
+    assert np.array_equal(torch_bits(pg.pool), want)
+    # and the plane that was restored is the oracle's own (so the whole drop -> quantize -> restore chain is checked)
+    if per_channel:
+        ref = oracle.quantize_channel(xb, bits, group, keep_idx=keep, Tp=qp.Tp, asym=asym)
+    elif asym:
+        ref = oracle.quantize_asym(xb, bits, group, keep_idx=keep, Tp=qp.Tp)
+    else:
+        ref = oracle.quantize(xb, bits, group, keep_idx=keep, Tp=qp.Tp) + (None,)
+    _check_plane(qp, ref)
+
+
+def test_scatter_restore_errors():
+    kvp = _kvp()
+    _say("scatter errors")
+    L, T, H, D, k = 1, 64, 2, 128, 16
+    qp = kvp.alloc_qplane(L, k, H, D, 4, 64, DEV)
+    qp.codes.zero_()
+    qp.scales.zero_()
+    bt, nb = workloads.make_block_table(T, 16, seed=0, device=DEV)
+    pg = kvp.alloc_paged(L, T, H, D, bt, nb, 16)
+    keep = torch.arange(k, dtype=torch.int32, device=DEV).repeat(L, H, 1).contiguous()
+    kvp.kvp_dequantize_paged_scatter(qp, keep, pg)
+    with pytest.raises(ValueError):
+        kvp.kvp_dequantize_paged_scatter(qp, keep[:, :, :8].contiguous(), pg)
+    small = kvp.alloc_paged(L, 8, H, D, bt[:1].contiguous(), nb, 16)     # pool shorter than the plane
+    with pytest.raises(kvp.KVPError) as e:
+        kvp.kvp_dequantize_paged_scatter(qp, keep, small)
+    assert e.value.code == -3
+    torch.cuda.synchronize()
