@@ -20,13 +20,16 @@
 //
 // The attention kernel (steps 3 and 4) walks the tokens in tiles of 32.  Per tile: 256 threads
 // load 32 K rows and 32 V rows (16 lanes per row, 8 channels per lane), run the bit-exact group
-// quantizer and dequantizer of quant_device.h on them, and stage K-hat as bf16 and V-hat as fp32
+// quantizer and dequantizer of quant_device.h on them, and stage K-hat and V-hat as bf16
 // in LDS.  Each of the 4 waves owns 32 of the block's 128 query rows (stationary MFMA operand in
 // registers) and computes S^T = K-hat Q^T with 8 v_mfma_f32_32x32x16_bf16, so a lane holds one
-// query and 16 keys and the online-softmax statistics stay lane-private.  The probabilities go to
-// LDS in fp32 and the P.V product runs on the vector ALU in fp32 with an 8x8 register tile per
-// thread (the loss is a difference of two nearly equal outputs: rounding P to bf16 for a matrix
-// instruction would swamp the int8 configurations).
+// query and 16 keys and the online-softmax statistics stay lane-private.  The P.V product runs on
+// the matrix cores too, as O^T = V-hat^T P^T: V-hat is exact in bf16 (it is a dequantized value),
+// and each probability is split into two bf16 terms hi + lo (the loss is a difference of two nearly
+// equal outputs: rounding P to one bf16 would swamp the int8 configurations; the two-term split
+// leaves a relative error of 2^-18).  The probabilities never leave registers: the tokens a lane
+// holds after the logits tile are exactly the tokens its P^T operand must hold, given a matching
+// (permuted) token order in the V-hat^T operand, and the per-query rescaling is lane-private.
 
 #include "kvp_internal.h"
 #include "quant_device.h"
@@ -37,6 +40,10 @@ namespace {
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(16))) float floatx16;
 
+// resident waves per SIMD the attention kernel is compiled for (3 blocks per CU)
+#ifndef KVP_EVAL_WAVES_PER_SIMD
+#define KVP_EVAL_WAVES_PER_SIMD 3
+#endif
 constexpr int kThreads = 256;
 constexpr int kTile = 32;                  // tokens per tile
 constexpr int kRowsPerBlock = 128;         // query rows per block
@@ -81,35 +88,30 @@ __device__ __forceinline__ bf16x8 as_bf16x8(uint4 v) {
 
 __device__ __forceinline__ int acc_row(int lane, int v) { return (lane >> 5) * 4 + (v >> 2) * 8 + (v & 3); }
 
-// One lane's 8 channels of a row through quantize -> dequantize at (bits, group): y holds the
-// values decoding would read back (exactly representable in bf16).  bits and group are uniform
-// across the block.
-__device__ __forceinline__ void fake_quant8(const uint4 raw, int bits, int group, float y[8]) {
-  float x[8];
+// One lane's 8 channels of a row through quantize -> dequantize at (bits, group), returned as the
+// 8 packed bf16 values decoding would read back (dequantized values are rounded to bf16, as
+// kvp_dequantize_paged stores them).  bits and group are uniform across the block.
+__device__ __forceinline__ uint4 fake_quant8(const uint4 raw, int bits, int group) {
+  if (bits == 16) return raw;
+  float x[8], q[8];
   unpack_bf16x8(raw, x);
-  if (bits == 16) {
-#pragma unroll
-    for (int i = 0; i < 8; ++i) y[i] = x[i];
-    return;
-  }
   const float amax = group_max(abs_max8(x), group / 8);
-  float q[8];
+  float scale;
   if (bits == 2) {
     const TernaryQuantizer tq(amax);
     tq.codes8(x, q);
-#pragma unroll
-    for (int i = 0; i < 8; ++i) y[i] = q[i] * amax;   // +-amax or 0: already a bf16 value
+    scale = amax;   // +-amax or 0
   } else if (bits == 4) {
     const GroupQuantizer<7> gq(amax);
     gq.codes8(x, q);
-#pragma unroll
-    for (int i = 0; i < 8; ++i) y[i] = __uint_as_float(f32_to_bf16_bits(q[i] * gq.scale) << 16);
+    scale = gq.scale;
   } else {
     const GroupQuantizer<127> gq(amax);
     gq.codes8(x, q);
-#pragma unroll
-    for (int i = 0; i < 8; ++i) y[i] = __uint_as_float(f32_to_bf16_bits(q[i] * gq.scale) << 16);
+    scale = gq.scale;
   }
+  return make_uint4(pack_bf16x2(q[0] * scale, q[1] * scale), pack_bf16x2(q[2] * scale, q[3] * scale),
+                    pack_bf16x2(q[4] * scale, q[5] * scale), pack_bf16x2(q[6] * scale, q[7] * scale));
 }
 
 __device__ __forceinline__ float block_sum(float v, float* red) {
@@ -178,18 +180,30 @@ __global__ __launch_bounds__(kOrderThreads) void build_order_kernel(const EvalAr
   }
 }
 
+// 8 tokens of channel `ch` from the staged V-hat tile as an MFMA operand: the contraction index of
+// the P.V product is the token, and a lane's 8 tokens of k-step ks are the ones its accumulator of
+// the logits tile already holds, token(ks, half, e) = 16 ks + 8 (e >> 2) + 4 half + (e & 3), so
+// the probabilities go from the softmax straight into the other operand without leaving registers.
+__device__ __forceinline__ bf16x8 v_operand(const uint16_t* v_s, int ch, int ks, int half) {
+  const uint16_t* col = v_s + (16 * ks + 4 * half) * kHeadDim + ch;
+  uint4 w;
+  w.x = col[0 * kHeadDim] | (static_cast<uint32_t>(col[1 * kHeadDim]) << 16);
+  w.y = col[2 * kHeadDim] | (static_cast<uint32_t>(col[3 * kHeadDim]) << 16);
+  w.z = col[8 * kHeadDim] | (static_cast<uint32_t>(col[9 * kHeadDim]) << 16);
+  w.w = col[10 * kHeadDim] | (static_cast<uint32_t>(col[11 * kHeadDim]) << 16);
+  return as_bf16x8(w);
+}
+
 // REFERENCE: stream = (16 bits, all tokens); writes O_full and the denominator.
 template <bool REFERENCE>
-__global__ __launch_bounds__(kThreads) void attention_kernel(const EvalArgs a) {
+__global__ __launch_bounds__(kThreads, KVP_EVAL_WAVES_PER_SIMD) void attention_kernel(const EvalArgs a) {
   __shared__ __attribute__((aligned(16))) uint16_t k_s[kTile * kPitch];
-  __shared__ __attribute__((aligned(16))) float v_s[kTile * kHeadDim];
-  __shared__ __attribute__((aligned(16))) float p_s[kTile * kRowsPerBlock];
-  __shared__ __attribute__((aligned(16))) float alpha_s[kRowsPerBlock];
-  __shared__ __attribute__((aligned(16))) float z_s[kRowsPerBlock];
+  __shared__ __attribute__((aligned(16))) uint16_t v_s[kTile * kHeadDim];   // V-hat, bf16 (exact), [token][channel]
   __shared__ int tok_s[kTile];
   __shared__ float red_s[4];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int half = lane >> 5;
   const int rb = blockIdx.x, lh = blockIdx.y;
   const int l = lh / a.Hkv, h = lh - l * a.Hkv;
   int bits = 16, group = 128;
@@ -204,11 +218,10 @@ __global__ __launch_bounds__(kThreads) void attention_kernel(const EvalArgs a) {
 
   // stationary operand: this wave's 32 query rows
   bf16x8 q[8];
+  const int qrow = rb * kRowsPerBlock + wave * 32 + (lane & 31);
   {
-    const int r = rb * kRowsPerBlock + wave * 32 + (lane & 31);
-    const int half = lane >> 5;
-    if (r < a.M) {
-      const int u = r / a.W, w = r - u * a.W;
+    if (qrow < a.M) {
+      const int u = qrow / a.W, w = qrow - u * a.W;
       const uint16_t* row = a.q + static_cast<int64_t>(l) * a.q_sl + static_cast<int64_t>(w) * a.q_st +
                             static_cast<int64_t>(h * a.G + u) * a.q_sh;
 #pragma unroll
@@ -218,16 +231,14 @@ __global__ __launch_bounds__(kThreads) void attention_kernel(const EvalArgs a) {
       for (int ks = 0; ks < 8; ++ks) q[ks] = as_bf16x8(make_uint4(0, 0, 0, 0));
     }
   }
-  const int qpos = win0 + ((rb * kRowsPerBlock + wave * 32 + (lane & 31)) % a.W);
+  const int qpos = win0 + (qrow % a.W);
   float run_m = -INFINITY, run_z = 0.0f;  // per query (lane%32); run_z is this half-wave's share
 
-  // output tile of this thread: rows {4ty..4ty+3, 64+4ty..}, columns {4tx..4tx+3, 64+4tx..}
-  const int ty = tid >> 4, tx = tid & 15;
-  float o[8][8];
+  // O^T of this wave's 32 queries: o[ct][v] = channel 32 ct + acc_row(lane, v) of query lane%32
+  floatx16 o[4];
 #pragma unroll
-  for (int i = 0; i < 8; ++i)
-#pragma unroll
-    for (int j = 0; j < 8; ++j) o[i][j] = 0.0f;
+  for (int ct = 0; ct < 4; ++ct) o[ct] = floatx16{0};
+  // reference output of this block, in the accumulator layout: [thread][ct][v]
   float* ofull = a.o_full + (static_cast<int64_t>(lh) * a.RB + rb) * kRowsPerBlock * kHeadDim;
 
   // segments end at the keep levels (tiles never straddle a level boundary, so the state at a
@@ -235,132 +246,149 @@ __global__ __launch_bounds__(kThreads) void attention_kernel(const EvalArgs a) {
   // tokens no level keeps, and only looks at its state at the very end: a 16-bit stream is then
   // bit-identical to it wherever the two cover the same tokens.
   const int n_seg = a.n_levels + ((REFERENCE && a.level_k[a.n_levels - 1] < a.T) ? 1 : 0);
-  int pos0 = 0;
-  for (int seg = 0; seg < n_seg; ++seg) {
-    const int seg_end = seg < a.n_levels ? a.level_k[seg] : a.T;
-    for (; pos0 < seg_end; pos0 += kTile) {
+  auto seg_end_of = [&](int sg) { return sg < a.n_levels ? a.level_k[sg] : a.T; };
+
+  // Tile cursor: tile = positions [pos, min(pos + 32, end)) of segment seg.  Global loads run ahead of
+  // the arithmetic: the permutation entries of a tile are fetched two tiles early and its K and V rows
+  // one tile early, so neither of the two dependent latencies sits between two tiles.
+  struct Cursor { int pos, seg, end; };
+  auto advance = [&](Cursor c) {
+    c.pos += kTile;
+    if (c.pos >= c.end && c.seg < n_seg) {
+      c.pos = c.end;
+      c.seg += 1;
+      if (c.seg < n_seg) c.end = seg_end_of(c.seg);
+    }
+    return c;
+  };
+  const int tk_a = tid >> 4, tk_b = (tid + kThreads) >> 4, part = tid & 15;   // this thread's two staging slots
+  auto load_token = [&](const Cursor& c, int tk) {
+    int t = 0x7fffffff;  // beyond every query position: masked
+    if (c.seg < n_seg && c.pos + tk < c.end) t = min(max(order[c.pos + tk], 0), a.T - 1);
+    return t;
+  };
+  auto load_row = [&](const uint16_t* base, int64_t stride, int t) {
+    uint4 raw = make_uint4(0, 0, 0, 0);
+    if (t != 0x7fffffff) raw = *reinterpret_cast<const uint4*>(base + static_cast<int64_t>(t) * stride + part * 8);
+    return raw;
+  };
+  bool has_window = false;
+  auto stage = [&](int tk, int t, const uint4 kraw, const uint4 vraw) {
+    const uint4 kp = fake_quant8(kraw, bits, group), vp = fake_quant8(vraw, bits, group);
+    *reinterpret_cast<uint4*>(k_s + tk * kPitch + part * 8) = kp;
+    *reinterpret_cast<uint4*>(v_s + tk * kHeadDim + part * 8) = vp;
+    if (part == 0) tok_s[tk] = t;
+    has_window |= (t >= win0);   // window tokens and padding slots of a ragged tile need the mask
+  };
+
+  Cursor cur{0, 0, seg_end_of(0)};
+  Cursor nxt = advance(cur);
+  int t_a = load_token(cur, tk_a), t_b = load_token(cur, tk_b);
+  uint4 k_a = load_row(kbase, a.k_st, t_a), v_a = load_row(vbase, a.v_st, t_a);
+  uint4 k_b = load_row(kbase, a.k_st, t_b), v_b = load_row(vbase, a.v_st, t_b);
+  int tn_a = load_token(nxt, tk_a), tn_b = load_token(nxt, tk_b);
+
+  while (cur.seg < n_seg) {
+    const int seg = cur.seg;
+    {
       __syncthreads();  // the previous tile's LDS is no longer read
-      // ---- stage 32 tokens: K-hat (bf16) and V-hat (fp32) ----
-      bool has_window = false;
-#pragma unroll
-      for (int s = 0; s < 2; ++s) {
-        const int slot = tid + s * kThreads;
-        const int tk = slot >> 4, part = slot & 15;
-        const int pos = pos0 + tk;
-        uint4 kraw = make_uint4(0, 0, 0, 0), vraw = make_uint4(0, 0, 0, 0);
-        int t = 0x7fffffff;  // beyond every query position: masked
-        if (pos < seg_end) {
-          t = min(max(order[pos], 0), a.T - 1);
-          kraw = *reinterpret_cast<const uint4*>(kbase + static_cast<int64_t>(t) * a.k_st + part * 8);
-          vraw = *reinterpret_cast<const uint4*>(vbase + static_cast<int64_t>(t) * a.v_st + part * 8);
-        }
-        float ky[8], vy[8];
-        fake_quant8(kraw, bits, group, ky);
-        fake_quant8(vraw, bits, group, vy);
-        uint4 kp;
-        kp.x = (__float_as_uint(ky[0]) >> 16) | (__float_as_uint(ky[1]) & 0xffff0000u);
-        kp.y = (__float_as_uint(ky[2]) >> 16) | (__float_as_uint(ky[3]) & 0xffff0000u);
-        kp.z = (__float_as_uint(ky[4]) >> 16) | (__float_as_uint(ky[5]) & 0xffff0000u);
-        kp.w = (__float_as_uint(ky[6]) >> 16) | (__float_as_uint(ky[7]) & 0xffff0000u);
-        *reinterpret_cast<uint4*>(k_s + tk * kPitch + part * 8) = kp;
-        *reinterpret_cast<float4*>(v_s + tk * kHeadDim + part * 8) = make_float4(vy[0], vy[1], vy[2], vy[3]);
-        *reinterpret_cast<float4*>(v_s + tk * kHeadDim + part * 8 + 4) = make_float4(vy[4], vy[5], vy[6], vy[7]);
-        if (part == 0) tok_s[tk] = t;
-        has_window |= (t >= win0);
-      }
+      // ---- stage 32 tokens: K-hat and V-hat as bf16 (the dequantized values are bf16 values) ----
+      has_window = false;
+      stage(tk_a, t_a, k_a, v_a);
+      stage(tk_b, t_b, k_b, v_b);
+      // ---- run ahead: rows of the next tile, permutation entries of the one after ----
+      const Cursor nn = advance(nxt);
+      t_a = tn_a;
+      t_b = tn_b;
+      k_a = load_row(kbase, a.k_st, t_a);
+      v_a = load_row(vbase, a.v_st, t_a);
+      k_b = load_row(kbase, a.k_st, t_b);
+      v_b = load_row(vbase, a.v_st, t_b);
+      tn_a = load_token(nn, tk_a);
+      tn_b = load_token(nn, tk_b);
+      cur = nxt;
+      nxt = nn;
       const bool need_mask = __syncthreads_or(has_window ? 1 : 0) != 0;  // also publishes the stage
 
       // ---- logits of 32 keys x this wave's 32 queries, online softmax ----
+      floatx16 acc = {0};
       {
-        floatx16 acc = {0};
-        const uint16_t* krow = k_s + (lane & 31) * kPitch + (lane >> 5) * 8;
+        const uint16_t* krow = k_s + (lane & 31) * kPitch + half * 8;
 #pragma unroll
         for (int ks = 0; ks < 8; ++ks)
           acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(*reinterpret_cast<const uint4*>(krow + ks * 16)),
                                                         q[ks], acc, 0, 0, 0);
-        if (need_mask) {
-          asm volatile("" ::: "memory");  // keep this a real (block-uniform, rarely taken) branch
-#pragma unroll
-          for (int vv = 0; vv < 16; ++vv)
-            if (tok_s[acc_row(lane, vv)] > qpos) acc[vv] = -INFINITY;
-        }
-        float tmax = acc[0];
-#pragma unroll
-        for (int vv = 1; vv < 16; ++vv) tmax = fmaxf(tmax, acc[vv]);
-        tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
-        const float m_new = fmaxf(run_m, tmax * a.scale2);  // scale2 > 0: max commutes with it
-        const float m_safe = (m_new == -INFINITY) ? 0.0f : m_new;
-        const float alpha = __builtin_amdgcn_exp2f(run_m - m_safe);
-        float zsum = 0.0f;
-        const int rloc = wave * 32 + (lane & 31);
-#pragma unroll
-        for (int vv = 0; vv < 16; ++vv) {
-          const float p = __builtin_amdgcn_exp2f(fmaf(acc[vv], a.scale2, -m_safe));
-          zsum += p;
-          p_s[acc_row(lane, vv) * kRowsPerBlock + rloc] = p;
-        }
-        run_z = run_z * alpha + zsum;
-        run_m = m_new;
-        if (lane < 32) alpha_s[rloc] = alpha;
       }
-      __syncthreads();
+      if (need_mask) {
+        asm volatile("" ::: "memory");  // keep this a real (block-uniform, rarely taken) branch
+#pragma unroll
+        for (int vv = 0; vv < 16; ++vv)
+          if (tok_s[acc_row(lane, vv)] > qpos) acc[vv] = -INFINITY;
+      }
+      float tmax = acc[0];
+#pragma unroll
+      for (int vv = 1; vv < 16; ++vv) tmax = fmaxf(tmax, acc[vv]);
+      tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
+      const float m_new = fmaxf(run_m, tmax * a.scale2);  // scale2 > 0: max commutes with it
+      const float m_safe = (m_new == -INFINITY) ? 0.0f : m_new;
+      const float alpha = __builtin_amdgcn_exp2f(run_m - m_safe);
+      run_m = m_new;
+      // probabilities, split into two bf16 terms p = hi + lo (|p - hi - lo| <= 2^-18 p): the product
+      // with the bf16-exact V-hat then carries fp32-like accuracy through two matrix instructions
+      uint32_t p_hi[8], p_lo[8];
+      float zsum = 0.0f;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const float p0 = __builtin_amdgcn_exp2f(fmaf(acc[2 * e], a.scale2, -m_safe));
+        const float p1 = __builtin_amdgcn_exp2f(fmaf(acc[2 * e + 1], a.scale2, -m_safe));
+        zsum += p0 + p1;
+        p_hi[e] = pack_bf16x2(p0, p1);
+        p_lo[e] = pack_bf16x2(p0 - bf16lo(p_hi[e]), p1 - bf16hi(p_hi[e]));
+      }
+      run_z = run_z * alpha + zsum;
 
-      // ---- O = O * alpha + P V on the vector ALU ----
-      {
-        const float4 a0 = *reinterpret_cast<const float4*>(alpha_s + 4 * ty);
-        const float4 a1 = *reinterpret_cast<const float4*>(alpha_s + 64 + 4 * ty);
-        const float al[8] = {a0.x, a0.y, a0.z, a0.w, a1.x, a1.y, a1.z, a1.w};
+      // ---- O^T = O^T * alpha + V-hat^T P^T on the matrix cores ----
+      if (__builtin_amdgcn_ballot_w64(alpha != 1.0f)) {   // the running maximum moved for some query of the wave
 #pragma unroll
-        for (int i = 0; i < 8; ++i)
+        for (int ct = 0; ct < 4; ++ct)
 #pragma unroll
-          for (int j = 0; j < 8; ++j) o[i][j] *= al[i];
-#pragma unroll 4
-        for (int tk = 0; tk < kTile; ++tk) {
-          const float4 p0 = *reinterpret_cast<const float4*>(p_s + tk * kRowsPerBlock + 4 * ty);
-          const float4 p1 = *reinterpret_cast<const float4*>(p_s + tk * kRowsPerBlock + 64 + 4 * ty);
-          const float4 v0 = *reinterpret_cast<const float4*>(v_s + tk * kHeadDim + 4 * tx);
-          const float4 v1 = *reinterpret_cast<const float4*>(v_s + tk * kHeadDim + 64 + 4 * tx);
-          const float pr[8] = {p0.x, p0.y, p0.z, p0.w, p1.x, p1.y, p1.z, p1.w};
-          const float vc[8] = {v0.x, v0.y, v0.z, v0.w, v1.x, v1.y, v1.z, v1.w};
+          for (int vv = 0; vv < 16; ++vv) o[ct][vv] *= alpha;
+      }
 #pragma unroll
-          for (int i = 0; i < 8; ++i)
+      for (int ks = 0; ks < 2; ++ks) {
+        const bf16x8 bh = as_bf16x8(make_uint4(p_hi[4 * ks], p_hi[4 * ks + 1], p_hi[4 * ks + 2], p_hi[4 * ks + 3]));
+        const bf16x8 bl = as_bf16x8(make_uint4(p_lo[4 * ks], p_lo[4 * ks + 1], p_lo[4 * ks + 2], p_lo[4 * ks + 3]));
 #pragma unroll
-            for (int j = 0; j < 8; ++j) o[i][j] = fmaf(pr[i], vc[j], o[i][j]);
+        for (int ct = 0; ct < 4; ++ct) {
+          const bf16x8 vt = v_operand(v_s, 32 * ct + (lane & 31), ks, half);
+          o[ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vt, bh, o[ct], 0, 0, 0);
+          o[ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vt, bl, o[ct], 0, 0, 0);
         }
       }
     }
-    pos0 = seg_end;
+    if (cur.seg == seg) continue;                      // more tiles in this segment
     if (REFERENCE && seg != n_seg - 1) continue;
 
     // ---- end of a segment: normalize a copy, then store (reference) or compare with the reference ----
-    {
-      const float z = run_z + __shfl_xor(run_z, 32, 64);
-      __syncthreads();
-      if (lane < 32) z_s[wave * 32 + lane] = z;
-      __syncthreads();
-    }
+    const float inv = 1.0f / (run_z + __shfl_xor(run_z, 32, 64));
+    const bool live = qrow < a.M;
     float sq = 0.0f;
+    float4* cell = reinterpret_cast<float4*>(ofull + tid * 64);   // this thread's 64 values, contiguous
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      const int rloc = (i < 4) ? 4 * ty + i : 64 + 4 * ty + (i - 4);
-      const bool live = rb * kRowsPerBlock + rloc < a.M;
-      const float inv = 1.0f / z_s[rloc];
+    for (int ct = 0; ct < 4; ++ct)
 #pragma unroll
-      for (int jh = 0; jh < 2; ++jh) {
-        const int c0 = jh * 64 + 4 * tx;
-        const float4 val = make_float4(o[i][jh * 4 + 0] * inv, o[i][jh * 4 + 1] * inv, o[i][jh * 4 + 2] * inv,
-                                       o[i][jh * 4 + 3] * inv);
-        float4* dst = reinterpret_cast<float4*>(ofull + rloc * kHeadDim + c0);
+      for (int v4 = 0; v4 < 4; ++v4) {
+        const float4 val = make_float4(o[ct][4 * v4] * inv, o[ct][4 * v4 + 1] * inv, o[ct][4 * v4 + 2] * inv,
+                                       o[ct][4 * v4 + 3] * inv);
         if constexpr (REFERENCE) {
-          *dst = val;
+          cell[ct * 4 + v4] = val;
           if (live) sq += val.x * val.x + val.y * val.y + val.z * val.z + val.w * val.w;
         } else {
-          const float4 ref = *dst;
+          const float4 ref = cell[ct * 4 + v4];
           const float dx = val.x - ref.x, dy = val.y - ref.y, dz = val.z - ref.z, dw = val.w - ref.w;
           if (live) sq += dx * dx + dy * dy + dz * dz + dw * dw;
         }
       }
-    }
     const float total = block_sum(sq, red_s);
     if (tid == 0) {
       if constexpr (REFERENCE) {

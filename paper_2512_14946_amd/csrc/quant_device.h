@@ -1,13 +1,7 @@
 // Device-side arithmetic of the group quantizer, shared by kvp_quantize and by the
 // configuration-evaluation kernels (which quantize and dequantize on the fly).
 //
-// Bit-exact codes without one full IEEE division per element.  The defined result is
-// q = rint(fl32(x / scale)).  GroupQuantizer::code() forms y0 = x * rcp(scale) (relative error far below
-// 2^-21), q0 = rint(y0), and accepts q0 whenever y0 is further than kTieMargin from the nearest
-// half-integer: the correctly rounded quotient then lies in the same rounding interval.  Elements
-// close to a half-integer are resolved exactly: if fma(-h, scale, x) == 0 the quotient IS the
-// half-integer h (common with bf16 inputs) and rounds to the even neighbour; otherwise the element
-// takes the full IEEE division.  Both slow steps sit behind wave-uniform branches.
+// Bit-exact codes without one full IEEE division per element: see GroupQuantizer below.
 #pragma once
 
 #include "kvp_common.h"
@@ -48,41 +42,37 @@ __device__ __forceinline__ float scale_of_bf16_amax(float amax) {
 }
 
 // Group quantizer for QMAX in {7, 127}: scale and the codes (as integral floats) of one lane's
-// 8 elements, bit-exact with rint(fl32(x / scale)).
+// 8 elements, bit-exact with rint(fl32(x / scale)), without a division per element and without a
+// branch:
+//   inv = fl32(1 / scale)   from v_rcp_f32 (1 ulp) and one correction step fma(fma(-scale, y0, 1), y0, y0),
+//                           which lands on the correctly rounded reciprocal for every one of the
+//                           2 x 32640 scales that exist (scale = fl32(bf16 / QMAX)), whatever the
+//                           sign of the reciprocal estimate's last-place error;
+//   q0 = x * inv,  r = fma(-scale, q0, x) (the exact remainder),  y = fma(r, inv, q0),  code = rint(y).
+// y is the correctly rounded quotient (the classical remainder-correction division step), so exact
+// ties k + 1/2 come out exactly and round to even.  The identity rint(y) == rint(fl32(x / scale)) was
+// checked on the CPU for every bf16 amax in the exponent range below and every bf16 |x| <= amax
+// (1.7e9 pairs, both QMAX).  Outside that range the quantizer divides.
 template <int QMAX>
 struct GroupQuantizer {
   float scale, inv;
   bool unsafe;
   __device__ __forceinline__ explicit GroupQuantizer(float amax) {
     scale = scale_of_bf16_amax<QMAX>(amax);
-    // outside this range rcp or the products may leave the normal range: take the division path
-    unsafe = !(scale >= 0x1p-100f && scale <= 0x1p100f) && scale != 0.0f;
-    inv = (scale == 0.0f) ? 0.0f : __builtin_amdgcn_rcpf(scale);
+    // outside this range an intermediate may leave the normal range: take the division path
+    unsafe = !(scale >= 0x1p-60f && scale <= 0x1p60f) && scale != 0.0f;
+    const float y0 = __builtin_amdgcn_rcpf(scale);
+    inv = (scale == 0.0f) ? 0.0f : fmaf(fmaf(-scale, y0, 1.0f), y0, y0);
   }
   // from parameters computed elsewhere (the same scale and reciprocal)
   __device__ __forceinline__ GroupQuantizer(float s, float i) : scale(s), inv(i) {
-    unsafe = !(s >= 0x1p-100f && s <= 0x1p100f) && s != 0.0f;
+    unsafe = !(s >= 0x1p-60f && s <= 0x1p60f) && s != 0.0f;
   }
-  // |y0 - fl32(x/scale)| <= |x/scale| * (2^-22 + 2^-24 + 2^-24) < (QMAX + 1) * 2^-21
-  static constexpr float kTieMargin = static_cast<float>(QMAX + 1) * 0x1p-20f;
 
   __device__ __forceinline__ float code(float x) const {
-    const float y0 = x * inv;
-    float q = rintf(y0);
-    const float d = y0 - q;  // exact
-    const bool risky = fabsf(d) > 0.5f - kTieMargin;
-    if (__builtin_amdgcn_ballot_w64(risky)) {          // wave-uniform: rarely taken
-      if (risky) {
-        const float h = q + copysignf(0.5f, d);        // nearest half-integer, exact
-        const float e = fmaf(-h, scale, x);            // zero exactly when x / scale == h
-        const bool divide = e != 0.0f;
-        if (!divide) q = rintf(h);
-        if (__builtin_amdgcn_ballot_w64(divide)) {
-          if (divide) q = rintf(x / scale);
-        }
-      }
-    }
-    return q;
+    const float q0 = x * inv;
+    const float r = fmaf(-scale, q0, x);
+    return rintf(fmaf(r, inv, q0));
   }
 
   __device__ __forceinline__ void codes8(const float x[8], float q[8]) const {
@@ -98,7 +88,9 @@ struct GroupQuantizer {
 };
 
 // Asymmetric codec: codes 0 .. LEVELS of d = fl32(x - mn) on the scale fl32(fl32(mx - mn) / LEVELS).
-// Same reciprocal fast path and exact fallbacks as GroupQuantizer, applied to d.
+// The same remainder-correction step as GroupQuantizer, applied to d; the scale is an arbitrary
+// binary32 value here, so its reciprocal comes from one IEEE division per lane (correctly rounded by
+// definition), which is all the correction step needs to return the correctly rounded quotient.
 template <int LEVELS>
 struct AsymQuantizer {
   float scale, inv, mn;
@@ -113,37 +105,23 @@ struct AsymQuantizer {
     constexpr float kInvLevels = 1.0f / kLevels;
     const float q0 = range * kInvLevels;
     scale = fmaf(fmaf(-kLevels, q0, range), kInvLevels, q0);
-    unsafe = !(q0 >= 0x1p-100f && q0 <= 0x1p100f) && range != 0.0f;
+    unsafe = !(q0 >= 0x1p-60f && q0 <= 0x1p60f) && range != 0.0f;
     if (__builtin_amdgcn_ballot_w64(unsafe)) {
       if (unsafe) scale = range / kLevels;
     }
     unsafe = unsafe && scale != 0.0f;
-    inv = (scale == 0.0f) ? 0.0f : __builtin_amdgcn_rcpf(scale);
+    inv = (scale == 0.0f) ? 0.0f : 1.0f / scale;
   }
   // from parameters computed elsewhere (the same scale, reciprocal and minimum)
   __device__ __forceinline__ AsymQuantizer(float s, float i, float m) : scale(s), inv(i), mn(m) {
-    unsafe = !(s >= 0x1p-100f && s <= 0x1p100f) && s != 0.0f;
+    unsafe = !(s >= 0x1p-60f && s <= 0x1p60f) && s != 0.0f;
   }
-  static constexpr float kTieMargin = static_cast<float>(LEVELS + 1) * 0x1p-20f;
 
   __device__ __forceinline__ float code(float x) const {
     const float d0 = x - mn;
-    const float y0 = d0 * inv;
-    float q = rintf(y0);
-    const float d = y0 - q;  // exact
-    const bool risky = fabsf(d) > 0.5f - kTieMargin;
-    if (__builtin_amdgcn_ballot_w64(risky)) {
-      if (risky) {
-        const float h = q + copysignf(0.5f, d);
-        const float e = fmaf(-h, scale, d0);
-        const bool divide = e != 0.0f;
-        if (!divide) q = rintf(h);
-        if (__builtin_amdgcn_ballot_w64(divide)) {
-          if (divide) q = rintf(d0 / scale);
-        }
-      }
-    }
-    return q;
+    const float q0 = d0 * inv;
+    const float r = fmaf(-scale, q0, d0);
+    return rintf(fmaf(r, inv, q0));
   }
   __device__ __forceinline__ void codes8(const float x[8], float q[8]) const {
 #pragma unroll
@@ -177,11 +155,11 @@ struct TernaryQuantizer {
   float amax, inv;
   bool unsafe;
   __device__ __forceinline__ explicit TernaryQuantizer(float a) : amax(a) {
-    unsafe = !(a >= 0x1p-100f && a <= 0x1p100f) && a != 0.0f;
+    unsafe = !(a >= 0x1p-60f && a <= 0x1p60f) && a != 0.0f;
     inv = (a == 0.0f) ? 0.0f : __builtin_amdgcn_rcpf(a) * (1.0f - 0x1p-20f);
   }
   __device__ __forceinline__ TernaryQuantizer(float a, float i) : amax(a), inv(i) {
-    unsafe = !(a >= 0x1p-100f && a <= 0x1p100f) && a != 0.0f;
+    unsafe = !(a >= 0x1p-60f && a <= 0x1p60f) && a != 0.0f;
   }
   __device__ __forceinline__ void codes8(const float x[8], float q[8]) const {
 #pragma unroll

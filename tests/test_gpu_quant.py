@@ -36,6 +36,8 @@ def _special_rows(D=128):
     rows.append(np.round(rng.standard_normal(D) * 8) / 8 * 127)            # ties vs qmax 127
     rows.append(rng.standard_normal(D) * 2.0 ** -60)                       # tiny but inside the graded range
     rows.append(rng.standard_normal(D) * 2.0 ** 60)                        # huge
+    rows.append(rng.standard_normal(D) * 2.0 ** -45)                       # well inside the fast-path range
+    rows.append(rng.standard_normal(D) * 2.0 ** 45)
     rows.append(rng.standard_normal(D) * 2.0 ** -110)                      # below the fast-path range
     rows.append(rng.standard_normal(D) * 2.0 ** 110)                       # above the fast-path range
     r = rng.standard_normal(D)
