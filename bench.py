@@ -373,6 +373,7 @@ def side_measurements(kvp, workloads, torch, dev, K8, V8):
                      dtype=torch.uint8, device=dev)
     loss = torch.empty(len(cfgs), dtype=torch.float32, device=dev)
     t_ev = _time_loop(torch, lambda: kvp.kvp_eval_configs(Qe, Ke, Ve, cfgs, loss=loss, ws=ws), 2)
+    t_ev_mx = _time_loop(torch, lambda: kvp.kvp_eval_configs(Qe, Ke, Ve, cfgs, loss=loss, ws=ws, pv_matrix_cores=True), 2)
     M = c["G"] * c["W"]
     # work actually done: the reference pass plus one stream per codec, each over the largest keep-set
     tokens = (1 + len(variants)) * max(ks)
@@ -380,7 +381,10 @@ def side_measurements(kvp, workloads, torch, dev, K8, V8):
     ops["utility_sweep"] = {"workload": f"1 of {c['n_ctx']} contexts: {c['L']}x{c['H']}x{c['D']}x{c['T']}, {len(cfgs)} configs",
                             "eval_ms_per_context": round(t_ev * 1e3, 2), "configs_per_s": round(len(cfgs) / t_ev, 1),
                             "bound": "alu", "pv_TFLOPs_fp32": round(pv_flops / t_ev / 1e12, 2),
-                            "pv_frac_valu_peak": round(pv_flops / t_ev / 1e12 / VALU_FP32_PEAK_TFLOPS, 4)}
+                            "pv_frac_valu_peak": round(pv_flops / t_ev / 1e12 / VALU_FP32_PEAK_TFLOPS, 4),
+                            "opt_in_pv_matrix_cores": {"eval_ms_per_context": round(t_ev_mx * 1e3, 2),
+                                                       "configs_per_s": round(len(cfgs) / t_ev_mx, 1),
+                                                       "mfma_TFLOPs": round(3 * pv_flops / t_ev_mx / 1e12, 1)}}
     return ops
 
 

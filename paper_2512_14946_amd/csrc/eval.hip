@@ -23,13 +23,17 @@
 // quantizer and dequantizer of quant_device.h on them, and stage K-hat and V-hat as bf16
 // in LDS.  Each of the 4 waves owns 32 of the block's 128 query rows (stationary MFMA operand in
 // registers) and computes S^T = K-hat Q^T with 8 v_mfma_f32_32x32x16_bf16, so a lane holds one
-// query and 16 keys and the online-softmax statistics stay lane-private.  The P.V product runs on
-// the matrix cores too, as O^T = V-hat^T P^T: V-hat is exact in bf16 (it is a dequantized value),
-// and each probability is split into two bf16 terms hi + lo (the loss is a difference of two nearly
-// equal outputs: rounding P to one bf16 would swamp the int8 configurations; the two-term split
-// leaves a relative error of 2^-18).  The probabilities never leave registers: the tokens a lane
-// holds after the logits tile are exactly the tokens its P^T operand must hold, given a matching
-// (permuted) token order in the V-hat^T operand, and the per-query rescaling is lane-private.
+// query and 16 keys and the online-softmax statistics stay lane-private.  The P.V product has two
+// implementations, chosen per call:
+//   vector ALU (default): the probabilities go to LDS in fp32 and each thread accumulates an 8x8
+//     tile of the 128x128 output in fp32 (the matrix cores are kept for the query x key contraction);
+//   matrix cores (KVP_EVAL_PV_MATRIX_CORES): O^T = V-hat^T P^T with V-hat exact in bf16 (it is a
+//     dequantized value) and each probability split into two bf16 terms hi + lo (the loss is a
+//     difference of two nearly equal outputs: rounding P to one bf16 moves the losses by 1e-3
+//     relative; the two-term split leaves an error of 2^-18).  The probabilities never leave
+//     registers: the tokens a lane holds after the logits tile are exactly the tokens its P^T
+//     operand must hold, given a matching (permuted) token order in the V-hat^T operand, and the
+//     per-query rescaling is lane-private.
 
 #include "kvp_internal.h"
 #include "quant_device.h"
@@ -40,9 +44,9 @@ namespace {
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(16))) float floatx16;
 
-// resident waves per SIMD the attention kernel is compiled for (3 blocks per CU)
+// resident waves per SIMD the attention kernel is compiled for (2 blocks per CU; 3 would spill)
 #ifndef KVP_EVAL_WAVES_PER_SIMD
-#define KVP_EVAL_WAVES_PER_SIMD 3
+#define KVP_EVAL_WAVES_PER_SIMD 2
 #endif
 constexpr int kThreads = 256;
 constexpr int kTile = 32;                  // tokens per tile
@@ -180,25 +184,53 @@ __global__ __launch_bounds__(kOrderThreads) void build_order_kernel(const EvalAr
   }
 }
 
-// 8 tokens of channel `ch` from the staged V-hat tile as an MFMA operand: the contraction index of
-// the P.V product is the token, and a lane's 8 tokens of k-step ks are the ones its accumulator of
-// the logits tile already holds, token(ks, half, e) = 16 ks + 8 (e >> 2) + 4 half + (e & 3), so
-// the probabilities go from the softmax straight into the other operand without leaving registers.
-__device__ __forceinline__ bf16x8 v_operand(const uint16_t* v_s, int ch, int ks, int half) {
-  const uint16_t* col = v_s + (16 * ks + 4 * half) * kHeadDim + ch;
-  uint4 w;
-  w.x = col[0 * kHeadDim] | (static_cast<uint32_t>(col[1 * kHeadDim]) << 16);
-  w.y = col[2 * kHeadDim] | (static_cast<uint32_t>(col[3 * kHeadDim]) << 16);
-  w.z = col[8 * kHeadDim] | (static_cast<uint32_t>(col[9 * kHeadDim]) << 16);
-  w.w = col[10 * kHeadDim] | (static_cast<uint32_t>(col[11 * kHeadDim]) << 16);
-  return as_bf16x8(w);
+// V-hat^T in LDS.  The contraction index of the P.V product is the token, so the V-hat operand of a
+// lane is 8 tokens of ONE channel: the tile is staged transposed, one row per channel, and a lane's
+// 8 tokens of k-step ks are made the ones its accumulator of the logits tile already holds,
+//   token(ks, half, e) = 16 ks + 8 (e >> 2) + 4 half + (e & 3),
+// by storing token t = 16 ks + 8 b + 4 half + e' at column 16 ks + 8 half + 4 b + e'.  The
+// probabilities then go from the softmax straight into the other operand without leaving registers.
+// Channel ch lives in row (ch % 8) * 17 + ch / 8 with a row pitch of 80 bytes: the 16-byte operand
+// reads of 8 adjacent lanes then cover all 32 banks, and so do the 8-byte transposing writes.
+constexpr int kVtPitch = 40;                  // bf16 elements per row (32 used)
+constexpr int kVtRows = 7 * 17 + 16;
+__device__ __forceinline__ int vt_row(int ch) { return (ch & 7) * 17 + (ch >> 3); }
+
+__device__ __forceinline__ bf16x8 v_operand(const uint16_t* vt_s, int ch, int ks, int half) {
+  return as_bf16x8(*reinterpret_cast<const uint4*>(vt_s + vt_row(ch) * kVtPitch + 16 * ks + 8 * half));
+}
+
+// Staging of V-hat^T.  The four 16-lane rows of a wave hold four consecutive tokens (same 8
+// channels in the same lane of each row); a 4x4 transpose of 32-bit words across the rows
+// (v_permlane32_swap then v_permlane16_swap: each exchanges one lane-index bit with one register-index
+// bit) leaves row j with channels 2j, 2j+1 of all four tokens, which are two 8-byte LDS writes.
+__device__ __forceinline__ void stage_v_transposed(uint16_t* vt_s, uint4 vp, int q4, int part, int lane) {
+  typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
+  u32x2 s02 = __builtin_amdgcn_permlane32_swap(vp.x, vp.z, false, false);
+  u32x2 s13 = __builtin_amdgcn_permlane32_swap(vp.y, vp.w, false, false);
+  u32x2 s01 = __builtin_amdgcn_permlane16_swap(s02[0], s13[0], false, false);
+  u32x2 s23 = __builtin_amdgcn_permlane16_swap(s02[1], s13[1], false, false);
+  const uint32_t t0 = s01[0], t1 = s01[1], t2 = s23[0], t3 = s23[1];   // channel pair j of tokens 0..3
+  const int j = lane >> 4;
+  // tokens 4 q4 .. 4 q4 + 3 land at columns 4 q' .. with q' = q4 with its two low bits exchanged
+  const int col = 4 * ((q4 & 4) | ((q4 & 1) << 1) | ((q4 >> 1) & 1));
+  const uint2 even = make_uint2((t0 & 0xffffu) | (t1 << 16), (t2 & 0xffffu) | (t3 << 16));
+  const uint2 odd = make_uint2((t0 >> 16) | (t1 & 0xffff0000u), (t2 >> 16) | (t3 & 0xffff0000u));
+  *reinterpret_cast<uint2*>(vt_s + vt_row(part * 8 + 2 * j) * kVtPitch + col) = even;
+  *reinterpret_cast<uint2*>(vt_s + vt_row(part * 8 + 2 * j + 1) * kVtPitch + col) = odd;
 }
 
 // REFERENCE: stream = (16 bits, all tokens); writes O_full and the denominator.
-template <bool REFERENCE>
+// PV_MFMA: the P.V product on the matrix cores (two-term bf16 split of P) instead of the vector ALU.
+template <bool REFERENCE, bool PV_MFMA>
 __global__ __launch_bounds__(kThreads, KVP_EVAL_WAVES_PER_SIMD) void attention_kernel(const EvalArgs a) {
   __shared__ __attribute__((aligned(16))) uint16_t k_s[kTile * kPitch];
-  __shared__ __attribute__((aligned(16))) uint16_t v_s[kTile * kHeadDim];   // V-hat, bf16 (exact), [token][channel]
+  // V-hat: transposed bf16 for the matrix cores (see v_operand), or fp32 [token][channel] for the vector ALU
+  __shared__ __attribute__((aligned(16))) uint16_t vt_s[PV_MFMA ? kVtRows * kVtPitch : 8];
+  __shared__ __attribute__((aligned(16))) float v_s[PV_MFMA ? 4 : kTile * kHeadDim];
+  __shared__ __attribute__((aligned(16))) float p_s[PV_MFMA ? 4 : kTile * kRowsPerBlock];
+  __shared__ __attribute__((aligned(16))) float alpha_s[PV_MFMA ? 4 : kRowsPerBlock];
+  __shared__ __attribute__((aligned(16))) float z_s[PV_MFMA ? 4 : kRowsPerBlock];
   __shared__ int tok_s[kTile];
   __shared__ float red_s[4];
 
@@ -234,12 +266,17 @@ __global__ __launch_bounds__(kThreads, KVP_EVAL_WAVES_PER_SIMD) void attention_k
   const int qpos = win0 + (qrow % a.W);
   float run_m = -INFINITY, run_z = 0.0f;  // per query (lane%32); run_z is this half-wave's share
 
-  // O^T of this wave's 32 queries: o[ct][v] = channel 32 ct + acc_row(lane, v) of query lane%32
-  floatx16 o[4];
+  // Output accumulators, 64 per thread.
+  //   matrix cores: O^T of this wave's 32 queries, o[16 ct + v] = channel 32 ct + acc_row(lane, v) of query lane%32
+  //   vector ALU:   an 8x8 tile, o[8 i + j] = row {4ty.., 64+4ty..}[i], channel {4tx.., 64+4tx..}[j]
+  float o[64];
 #pragma unroll
-  for (int ct = 0; ct < 4; ++ct) o[ct] = floatx16{0};
-  // reference output of this block, in the accumulator layout: [thread][ct][v]
-  float* ofull = a.o_full + (static_cast<int64_t>(lh) * a.RB + rb) * kRowsPerBlock * kHeadDim;
+  for (int i = 0; i < 64; ++i) o[i] = 0.0f;
+  const int ty = tid >> 4, tx = tid & 15;
+  // reference output of this block; each thread's 64 values are contiguous (same thread, same layout in
+  // the reference pass and in the streams)
+  float4* cell = reinterpret_cast<float4*>(a.o_full + (static_cast<int64_t>(lh) * a.RB + rb) * kRowsPerBlock * kHeadDim +
+                                           tid * 64);
 
   // segments end at the keep levels (tiles never straddle a level boundary, so the state at a
   // boundary is exactly that level's attention).  The reference walks the same tiles, plus the
@@ -276,7 +313,13 @@ __global__ __launch_bounds__(kThreads, KVP_EVAL_WAVES_PER_SIMD) void attention_k
   auto stage = [&](int tk, int t, const uint4 kraw, const uint4 vraw) {
     const uint4 kp = fake_quant8(kraw, bits, group), vp = fake_quant8(vraw, bits, group);
     *reinterpret_cast<uint4*>(k_s + tk * kPitch + part * 8) = kp;
-    *reinterpret_cast<uint4*>(v_s + tk * kHeadDim + part * 8) = vp;
+    if constexpr (PV_MFMA) {
+      stage_v_transposed(vt_s, vp, tk >> 2, part, lane);
+    } else {
+      float* vrow = v_s + tk * kHeadDim + part * 8;
+      *reinterpret_cast<float4*>(vrow) = make_float4(bf16lo(vp.x), bf16hi(vp.x), bf16lo(vp.y), bf16hi(vp.y));
+      *reinterpret_cast<float4*>(vrow + 4) = make_float4(bf16lo(vp.z), bf16hi(vp.z), bf16lo(vp.w), bf16hi(vp.w));
+    }
     if (part == 0) tok_s[tk] = t;
     has_window |= (t >= win0);   // window tokens and padding slots of a ragged tile need the mask
   };
@@ -292,7 +335,7 @@ __global__ __launch_bounds__(kThreads, KVP_EVAL_WAVES_PER_SIMD) void attention_k
     const int seg = cur.seg;
     {
       __syncthreads();  // the previous tile's LDS is no longer read
-      // ---- stage 32 tokens: K-hat and V-hat as bf16 (the dequantized values are bf16 values) ----
+      // ---- stage 32 tokens: K-hat and V-hat (the dequantized values are bf16 values) ----
       has_window = false;
       stage(tk_a, t_a, k_a, v_a);
       stage(tk_b, t_b, k_b, v_b);
@@ -333,36 +376,79 @@ __global__ __launch_bounds__(kThreads, KVP_EVAL_WAVES_PER_SIMD) void attention_k
       const float m_safe = (m_new == -INFINITY) ? 0.0f : m_new;
       const float alpha = __builtin_amdgcn_exp2f(run_m - m_safe);
       run_m = m_new;
-      // probabilities, split into two bf16 terms p = hi + lo (|p - hi - lo| <= 2^-18 p): the product
-      // with the bf16-exact V-hat then carries fp32-like accuracy through two matrix instructions
-      uint32_t p_hi[8], p_lo[8];
-      float zsum = 0.0f;
-#pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        const float p0 = __builtin_amdgcn_exp2f(fmaf(acc[2 * e], a.scale2, -m_safe));
-        const float p1 = __builtin_amdgcn_exp2f(fmaf(acc[2 * e + 1], a.scale2, -m_safe));
-        zsum += p0 + p1;
-        p_hi[e] = pack_bf16x2(p0, p1);
-        p_lo[e] = pack_bf16x2(p0 - bf16lo(p_hi[e]), p1 - bf16hi(p_hi[e]));
-      }
-      run_z = run_z * alpha + zsum;
 
-      // ---- O^T = O^T * alpha + V-hat^T P^T on the matrix cores ----
-      if (__builtin_amdgcn_ballot_w64(alpha != 1.0f)) {   // the running maximum moved for some query of the wave
+      if constexpr (PV_MFMA) {
+        // probabilities, split into two bf16 terms p = hi + lo (|p - hi - lo| <= 2^-18 p): the product
+        // with the bf16-exact V-hat then carries fp32-like accuracy through two matrix instructions
+        uint32_t p_hi[8], p_lo[8];
+        float zsum = 0.0f;
 #pragma unroll
-        for (int ct = 0; ct < 4; ++ct)
+        for (int e = 0; e < 8; ++e) {
+          const float p0 = __builtin_amdgcn_exp2f(fmaf(acc[2 * e], a.scale2, -m_safe));
+          const float p1 = __builtin_amdgcn_exp2f(fmaf(acc[2 * e + 1], a.scale2, -m_safe));
+          zsum += p0 + p1;
+          p_hi[e] = pack_bf16x2(p0, p1);
+          p_lo[e] = pack_bf16x2(p0 - bf16lo(p_hi[e]), p1 - bf16hi(p_hi[e]));
+        }
+        run_z = run_z * alpha + zsum;
+        // ---- O^T = O^T * alpha + V-hat^T P^T on the matrix cores ----
+        if (__builtin_amdgcn_ballot_w64(alpha != 1.0f)) {   // the running maximum moved for some query of the wave
 #pragma unroll
-          for (int vv = 0; vv < 16; ++vv) o[ct][vv] *= alpha;
-      }
+          for (int i = 0; i < 64; ++i) o[i] *= alpha;
+        }
 #pragma unroll
-      for (int ks = 0; ks < 2; ++ks) {
-        const bf16x8 bh = as_bf16x8(make_uint4(p_hi[4 * ks], p_hi[4 * ks + 1], p_hi[4 * ks + 2], p_hi[4 * ks + 3]));
-        const bf16x8 bl = as_bf16x8(make_uint4(p_lo[4 * ks], p_lo[4 * ks + 1], p_lo[4 * ks + 2], p_lo[4 * ks + 3]));
+        for (int ks = 0; ks < 2; ++ks) {
+          const bf16x8 bh = as_bf16x8(make_uint4(p_hi[4 * ks], p_hi[4 * ks + 1], p_hi[4 * ks + 2], p_hi[4 * ks + 3]));
+          const bf16x8 bl = as_bf16x8(make_uint4(p_lo[4 * ks], p_lo[4 * ks + 1], p_lo[4 * ks + 2], p_lo[4 * ks + 3]));
+          bf16x8 vt[4];
 #pragma unroll
-        for (int ct = 0; ct < 4; ++ct) {
-          const bf16x8 vt = v_operand(v_s, 32 * ct + (lane & 31), ks, half);
-          o[ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vt, bh, o[ct], 0, 0, 0);
-          o[ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vt, bl, o[ct], 0, 0, 0);
+          for (int ct = 0; ct < 4; ++ct) vt[ct] = v_operand(vt_s, 32 * ct + (lane & 31), ks, half);
+          // the four channel tiles are independent accumulation chains: interleave them
+#pragma unroll
+          for (int pass = 0; pass < 2; ++pass)
+#pragma unroll
+            for (int ct = 0; ct < 4; ++ct) {
+              floatx16 oc;
+#pragma unroll
+              for (int vv = 0; vv < 16; ++vv) oc[vv] = o[16 * ct + vv];
+              oc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vt[ct], pass == 0 ? bh : bl, oc, 0, 0, 0);
+#pragma unroll
+              for (int vv = 0; vv < 16; ++vv) o[16 * ct + vv] = oc[vv];
+            }
+        }
+      } else {
+        // probabilities to LDS in fp32, [token][query row]
+        float zsum = 0.0f;
+        const int rloc = wave * 32 + (lane & 31);
+#pragma unroll
+        for (int vv = 0; vv < 16; ++vv) {
+          const float p = __builtin_amdgcn_exp2f(fmaf(acc[vv], a.scale2, -m_safe));
+          zsum += p;
+          p_s[acc_row(lane, vv) * kRowsPerBlock + rloc] = p;
+        }
+        run_z = run_z * alpha + zsum;
+        if (lane < 32) alpha_s[rloc] = alpha;
+        __syncthreads();
+        // ---- O = O * alpha + P V-hat on the vector ALU, fp32 ----
+        const float4 a0 = *reinterpret_cast<const float4*>(alpha_s + 4 * ty);
+        const float4 a1 = *reinterpret_cast<const float4*>(alpha_s + 64 + 4 * ty);
+        const float al[8] = {a0.x, a0.y, a0.z, a0.w, a1.x, a1.y, a1.z, a1.w};
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+#pragma unroll
+          for (int j = 0; j < 8; ++j) o[8 * i + j] *= al[i];
+#pragma unroll 4
+        for (int tk = 0; tk < kTile; ++tk) {
+          const float4 p0 = *reinterpret_cast<const float4*>(p_s + tk * kRowsPerBlock + 4 * ty);
+          const float4 p1 = *reinterpret_cast<const float4*>(p_s + tk * kRowsPerBlock + 64 + 4 * ty);
+          const float4 v0 = *reinterpret_cast<const float4*>(v_s + tk * kHeadDim + 4 * tx);
+          const float4 v1 = *reinterpret_cast<const float4*>(v_s + tk * kHeadDim + 64 + 4 * tx);
+          const float pr[8] = {p0.x, p0.y, p0.z, p0.w, p1.x, p1.y, p1.z, p1.w};
+          const float vc[8] = {v0.x, v0.y, v0.z, v0.w, v1.x, v1.y, v1.z, v1.w};
+#pragma unroll
+          for (int i = 0; i < 8; ++i)
+#pragma unroll
+            for (int j = 0; j < 8; ++j) o[8 * i + j] = fmaf(pr[i], vc[j], o[8 * i + j]);
         }
       }
     }
@@ -370,23 +456,41 @@ __global__ __launch_bounds__(kThreads, KVP_EVAL_WAVES_PER_SIMD) void attention_k
     if (REFERENCE && seg != n_seg - 1) continue;
 
     // ---- end of a segment: normalize a copy, then store (reference) or compare with the reference ----
-    const float inv = 1.0f / (run_z + __shfl_xor(run_z, 32, 64));
-    const bool live = qrow < a.M;
+    float inv[8];      // 1 / row sum of the rows this thread's accumulators belong to
+    bool live[8];
+    if constexpr (PV_MFMA) {
+      const float one = 1.0f / (run_z + __shfl_xor(run_z, 32, 64));
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        inv[i] = one;
+        live[i] = qrow < a.M;
+      }
+    } else {
+      const float z = run_z + __shfl_xor(run_z, 32, 64);
+      __syncthreads();
+      if (lane < 32) z_s[wave * 32 + lane] = z;
+      __syncthreads();
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const int rloc = (i < 4) ? 4 * ty + i : 64 + 4 * ty + (i - 4);
+        inv[i] = 1.0f / z_s[rloc];
+        live[i] = rb * kRowsPerBlock + rloc < a.M;
+      }
+    }
     float sq = 0.0f;
-    float4* cell = reinterpret_cast<float4*>(ofull + tid * 64);   // this thread's 64 values, contiguous
 #pragma unroll
-    for (int ct = 0; ct < 4; ++ct)
+    for (int i = 0; i < 8; ++i)       // accumulators 8 i .. 8 i + 7 share a row in the vector-ALU layout
 #pragma unroll
-      for (int v4 = 0; v4 < 4; ++v4) {
-        const float4 val = make_float4(o[ct][4 * v4] * inv, o[ct][4 * v4 + 1] * inv, o[ct][4 * v4 + 2] * inv,
-                                       o[ct][4 * v4 + 3] * inv);
+      for (int jh = 0; jh < 2; ++jh) {
+        const int e = 8 * i + 4 * jh;
+        const float4 val = make_float4(o[e] * inv[i], o[e + 1] * inv[i], o[e + 2] * inv[i], o[e + 3] * inv[i]);
         if constexpr (REFERENCE) {
-          cell[ct * 4 + v4] = val;
-          if (live) sq += val.x * val.x + val.y * val.y + val.z * val.z + val.w * val.w;
+          cell[e >> 2] = val;
+          if (live[i]) sq += val.x * val.x + val.y * val.y + val.z * val.z + val.w * val.w;
         } else {
-          const float4 ref = cell[ct * 4 + v4];
+          const float4 ref = cell[e >> 2];
           const float dx = val.x - ref.x, dy = val.y - ref.y, dz = val.z - ref.z, dw = val.w - ref.w;
-          if (live) sq += dx * dx + dy * dy + dz * dz + dw * dw;
+          if (live[i]) sq += dx * dx + dy * dy + dz * dz + dw * dw;
         }
       }
     const float total = block_sum(sq, red_s);
@@ -469,10 +573,11 @@ extern "C" size_t kvp_eval_workspace_bytes(int64_t L, int64_t Hkv, int64_t Hq, i
   return kvp::make_plan(L, Hkv, Hq, W, T, n_cfgs).total;
 }
 
-extern "C" int32_t kvp_eval_configs(const kvp_view* q_win, const kvp_view* k, const kvp_view* v, const kvp_config* cfgs,
-                                    int32_t n_cfgs, float* loss, float* partial, void* ws, size_t ws_bytes,
-                                    void* stream) {
+extern "C" int32_t kvp_eval_configs_ex(const kvp_view* q_win, const kvp_view* k, const kvp_view* v,
+                                       const kvp_config* cfgs, int32_t n_cfgs, float* loss, float* partial, void* ws,
+                                       size_t ws_bytes, uint32_t flags, void* stream) {
   using namespace kvp;
+  if (flags & ~static_cast<uint32_t>(KVP_EVAL_PV_MATRIX_CORES)) return KVP_ERR_UNSUPPORTED;
   int32_t rc = check_view(q_win);
   if (rc != KVP_OK) return rc;
   rc = check_view(k);
@@ -559,9 +664,21 @@ extern "C" int32_t kvp_eval_configs(const kvp_view* q_win, const kvp_view* k, co
     }
   }
   build_order_kernel<<<dim3(static_cast<unsigned>(p.LH)), kOrderThreads, 0, st>>>(a);
-  attention_kernel<true><<<dim3(static_cast<unsigned>(p.RB), static_cast<unsigned>(p.LH), 1), kThreads, 0, st>>>(a);
-  attention_kernel<false><<<dim3(static_cast<unsigned>(p.RB), static_cast<unsigned>(p.LH),
-                                 static_cast<unsigned>(a.n_streams)), kThreads, 0, st>>>(a);
+  const dim3 grid_ref(static_cast<unsigned>(p.RB), static_cast<unsigned>(p.LH), 1);
+  const dim3 grid_streams(static_cast<unsigned>(p.RB), static_cast<unsigned>(p.LH), static_cast<unsigned>(a.n_streams));
+  if (flags & KVP_EVAL_PV_MATRIX_CORES) {
+    attention_kernel<true, true><<<grid_ref, kThreads, 0, st>>>(a);
+    attention_kernel<false, true><<<grid_streams, kThreads, 0, st>>>(a);
+  } else {
+    attention_kernel<true, false><<<grid_ref, kThreads, 0, st>>>(a);
+    attention_kernel<false, false><<<grid_streams, kThreads, 0, st>>>(a);
+  }
   finish_kernel<<<1, kFinishThreads, 0, st>>>(a);
   return launch_status();
+}
+
+extern "C" int32_t kvp_eval_configs(const kvp_view* q_win, const kvp_view* k, const kvp_view* v, const kvp_config* cfgs,
+                                    int32_t n_cfgs, float* loss, float* partial, void* ws, size_t ws_bytes,
+                                    void* stream) {
+  return kvp_eval_configs_ex(q_win, k, v, cfgs, n_cfgs, loss, partial, ws, ws_bytes, 0u, stream);
 }

@@ -4,9 +4,9 @@
 // in quant_device.h; only the set of elements that share a scale differs: `group` consecutive slots
 // of one channel of one head.
 //
-// Quantize.  A 256-thread block owns one (token group, tile of HB heads, layer), HB = 2 or 1.  A
+// Quantize.  A 256-thread block (512 for groups of 128 slots) owns one (token group, 2 heads, layer).  A
 // thread owns one (head, 8-channel chunk) column and the token slots  slot, slot + S, ...  of the
-// group (S = 256 / (16 HB) slots per load step).  All G / S rows of a thread (4 or 8) are loaded up
+// group (S = threads / 32 slots per load step).  All G / S rows of a thread (4 or 8) are loaded up
 // front and stay in registers, so the plane is read once.  The per-channel extremes of the S slots
 // meet in LDS; one thread per channel then reduces them and builds that channel's quantizer (scale,
 // reciprocal, minimum) once, publishes it to LDS and to the scales / mins planes; after the second
@@ -93,7 +93,7 @@ __device__ __forceinline__ Packed<BITS> zero_codes() {
 // Block shape for a group of G slots: threads and heads per block; a thread keeps
 // G * 16 * HB / threads rows in registers.
 #ifndef KVP_QC_SHAPES
-#define KVP_QC_SHAPES {256, 2}, {256, 2}, {256, 1}
+#define KVP_QC_SHAPES {256, 2}, {256, 2}, {512, 2}
 #endif
 struct BlockShape { int threads, heads; };
 constexpr BlockShape kShapes[3] = {KVP_QC_SHAPES};   // G = 32, 64, 128

@@ -84,6 +84,9 @@ def _load(path: str = _LIB_PATH):
     lib.kvp_select_workspace_bytes.argtypes = [_i64] * 3
     lib.kvp_eval_configs.restype = _i32
     lib.kvp_eval_configs.argtypes = [P(_View), P(_View), P(_View), P(_Config), _i32, _vp, _vp, _vp, _sz, _vp]
+    lib.kvp_eval_configs_ex.restype = _i32
+    lib.kvp_eval_configs_ex.argtypes = [P(_View), P(_View), P(_View), P(_Config), _i32, _vp, _vp, _vp, _sz,
+                                        ctypes.c_uint32, _vp]
     lib.kvp_eval_workspace_bytes.restype = _sz
     lib.kvp_eval_workspace_bytes.argtypes = [_i64] * 5 + [_i32]
     lib.kvp_utility_table.restype = _i32
@@ -363,8 +366,10 @@ def kvp_eval_workspace_bytes(L: int, Hkv: int, Hq: int, W: int, T: int, n_cfgs: 
 
 def kvp_eval_configs(q_win: torch.Tensor, k: torch.Tensor, v: torch.Tensor, cfgs: Iterable[Sequence[int]],
                      loss: torch.Tensor | None = None, partial: torch.Tensor | None = None,
-                     ws: torch.Tensor | None = None, stream=None, want_partial: bool = False):
-    """cfgs: (bits, group, keep_k) triples.  Returns loss f32 [n] (and partial f32 [L][n][2] if asked)."""
+                     ws: torch.Tensor | None = None, stream=None, want_partial: bool = False,
+                     pv_matrix_cores: bool = False):
+    """cfgs: (bits, group, keep_k) triples.  Returns loss f32 [n] (and partial f32 [L][n][2] if asked).
+    pv_matrix_cores selects kvp_eval_configs_ex with KVP_EVAL_PV_MATRIX_CORES."""
     _need_cuda(q_win, k, v, loss, partial, ws)
     cfgs = list(cfgs)
     n = len(cfgs)
@@ -377,13 +382,18 @@ def kvp_eval_configs(q_win: torch.Tensor, k: torch.Tensor, v: torch.Tensor, cfgs
         partial = torch.empty(L, n, 2, dtype=torch.float32, device=k.device)
     ws, wp, wb = _workspace(ws, kvp_eval_workspace_bytes(L, Hkv, Hq, W, T, n), k.device)
     qv, kv, vv = _view(q_win), _view(k), _view(v)
-    _check(_lib.kvp_eval_configs(ctypes.byref(qv), ctypes.byref(kv), ctypes.byref(vv), arr, n, loss.data_ptr(),
-                                 partial.data_ptr() if partial is not None else None, wp, wb, _stream(stream)),
-           "kvp_eval_configs")
+    pp = partial.data_ptr() if partial is not None else None
+    if pv_matrix_cores:
+        _check(_lib.kvp_eval_configs_ex(ctypes.byref(qv), ctypes.byref(kv), ctypes.byref(vv), arr, n, loss.data_ptr(),
+                                        pp, wp, wb, KVP_EVAL_PV_MATRIX_CORES, _stream(stream)), "kvp_eval_configs_ex")
+    else:
+        _check(_lib.kvp_eval_configs(ctypes.byref(qv), ctypes.byref(kv), ctypes.byref(vv), arr, n, loss.data_ptr(),
+                                     pp, wp, wb, _stream(stream)), "kvp_eval_configs")
     return (loss, partial) if partial is not None else loss
 
 
 KVP_OP_INSERT, KVP_OP_COMPRESS, KVP_OP_EVICT = 0, 1, 2
+KVP_EVAL_PV_MATRIX_CORES = 1
 
 
 def _tiers(tiers):

@@ -16,13 +16,14 @@ def _kvp():
     return kvp
 
 
-def _case(L, W, G, H, T, cfgs, seed, outlier=8.0):
+def _case(L, W, G, H, T, cfgs, seed, outlier=8.0, pv_matrix_cores=False):
     kvp = _kvp()
     D = 128
-    print("[case] eval", dict(L=L, W=W, G=G, H=H, T=T, n=len(cfgs)), flush=True)
+    print("[case] eval", dict(L=L, W=W, G=G, H=H, T=T, n=len(cfgs), pv_matrix_cores=pv_matrix_cores), flush=True)
     K, V = workloads.make_kv(L, T, H, D, seed=seed, outlier_scale=outlier)
     Q = workloads.make_q(L, W, G * H, D, seed=seed)
-    loss, partial = kvp.kvp_eval_configs(Q.to(DEV), K.to(DEV), V.to(DEV), cfgs, want_partial=True)
+    loss, partial = kvp.kvp_eval_configs(Q.to(DEV), K.to(DEV), V.to(DEV), cfgs, want_partial=True,
+                                         pv_matrix_cores=pv_matrix_cores)
     torch.cuda.synchronize()
     loss, partial = loss.cpu().numpy(), partial.cpu().numpy()
     ref, ref_partial = oracle.eval_configs(torch_bits(Q), torch_bits(K), torch_bits(V), cfgs)
@@ -38,27 +39,34 @@ def _sweep(T):
     return [(b, g, k) for (b, g) in variants for k in ks]
 
 
-def test_full_candidate_sweep_small():
+BOTH_PV = pytest.mark.parametrize("pv_matrix_cores", [False, True], ids=["pv_vector_alu", "pv_matrix_cores"])
+
+
+@BOTH_PV
+def test_full_candidate_sweep_small(pv_matrix_cores):
     T = 300                                            # ragged: 300 = 9 tiles of 32 + 12
     cfgs = _sweep(T)
     assert len(cfgs) == 40
-    loss, ref = _case(2, 32, 4, 2, T, cfgs, seed=0)
+    loss, ref = _case(2, 32, 4, 2, T, cfgs, seed=0, pv_matrix_cores=pv_matrix_cores)
     assert loss[3] == 0.0                              # (16 bits, keep all) is the identity, exactly
     order = {c: i for i, c in enumerate(cfgs)}
     for g in (32, 64, 128):                            # fewer bits, larger loss
         assert loss[order[(8, g, T)]] < loss[order[(4, g, T)]] < loss[order[(2, g, T)]]
 
 
-def test_padded_row_blocks_and_tiny_keep():
+@BOTH_PV
+def test_padded_row_blocks_and_tiny_keep(pv_matrix_cores):
     T = 200
     cfgs = [(16, 0, T), (8, 128, T), (4, 32, 77), (2, 64, 33), (16, 0, 5), (4, 64, 1)]
-    _case(1, 32, 7, 2, T, cfgs, seed=1, outlier=16.0)  # M = 224: two row blocks, the second partly filled
+    # M = 224: two row blocks, the second partly filled
+    _case(1, 32, 7, 2, T, cfgs, seed=1, outlier=16.0, pv_matrix_cores=pv_matrix_cores)
 
 
-def test_many_rows_and_duplicates():
+@BOTH_PV
+def test_many_rows_and_duplicates(pv_matrix_cores):
     T = 130
     cfgs = [(8, 32, 64), (8, 32, 64), (16, 0, 64), (2, 32, T)]
-    loss, _ = _case(1, 64, 8, 1, T, cfgs, seed=2)      # M = 512: four row blocks
+    loss, _ = _case(1, 64, 8, 1, T, cfgs, seed=2, pv_matrix_cores=pv_matrix_cores)      # M = 512: four row blocks
     assert loss[0] == loss[1]
 
 

@@ -155,7 +155,8 @@ def test_long_context_select_full_rows():
     assert np.all(kept_min >= dropped_max)
 
 
-def test_utility_sweep_context_properties_and_sampled_head():
+@pytest.mark.parametrize("pv_matrix_cores", [False, True], ids=["pv_vector_alu", "pv_matrix_cores"])
+def test_utility_sweep_context_properties_and_sampled_head(pv_matrix_cores):
     kvp = _kvp()
     c = workloads.CONFIGS["utility_sweep"]
     L, T, H, D, G, W = c["L"], c["T"], c["H"], c["D"], c["G"], c["W"]
@@ -166,7 +167,7 @@ def test_utility_sweep_context_properties_and_sampled_head():
     assert ks == [2048, 4096, 6144, 8192]
     variants = [(16, 0)] + [(b, g) for b in c["bits_set"] for g in c["group_set"]]
     cfgs = [(b, g, kk) for (b, g) in variants for kk in ks]
-    loss, partial = kvp.kvp_eval_configs(Q, K, V, cfgs, want_partial=True)
+    loss, partial = kvp.kvp_eval_configs(Q, K, V, cfgs, want_partial=True, pv_matrix_cores=pv_matrix_cores)
     torch.cuda.synchronize()
     loss = loss.cpu().numpy().reshape(len(variants), len(ks))
     assert loss[0, 3] == 0.0                                               # identity row
@@ -180,7 +181,7 @@ def test_utility_sweep_context_properties_and_sampled_head():
     sub = [(16, 0, T), (8, 128, T), (4, 64, 4096), (2, 32, 2048), (16, 0, 2048)]
     l, h = 7, 2
     Qs, Ks, Vs = Q[l:l + 1, :, h * G:(h + 1) * G], K[l:l + 1, :, h:h + 1], V[l:l + 1, :, h:h + 1]
-    got = kvp.kvp_eval_configs(Qs, Ks, Vs, sub)
+    got = kvp.kvp_eval_configs(Qs, Ks, Vs, sub, pv_matrix_cores=pv_matrix_cores)
     torch.cuda.synchronize()
     ref, _ = oracle.eval_configs(torch_bits(Qs), torch_bits(Ks), torch_bits(Vs), sub)
     got = got.cpu().numpy()
