@@ -320,9 +320,9 @@ def side_measurements(kvp, workloads, torch, dev, K8, V8):
                          "keydiff_ms": round(tk * 1e3, 3), "keydiff_GBs_alg": round((2 * kb + sc8.numel() * 4) / tk / 1e9, 1),
                          "keydiff_frac_hbm": round((2 * kb + sc8.numel() * 4) / tk / 1e9 / HBM_PEAK_GBS, 4)}
     del sc8, wsk
-    # --- 70B-shaped drop + quantize pipeline on a 16-layer slice of the resident planes' shape ---
+    # --- 70B-shaped drop + quantize pipeline at its true shape (80 layers, 5 GiB of K and V) ---
     c = workloads.CONFIGS["llama3_70b_drop_int4"]
-    Ls = 16
+    Ls = c["L"]
     Kc, Vc = workloads.make_kv(Ls, c["T"], c["H"], c["D"], seed=0, device=dev)
     Qc = workloads.make_q(Ls, c["W"], c["G"] * c["H"], c["D"], seed=0, device=dev)
     k = kvp.kvp_keep_count(c["keep_ratio"], c["T"])
@@ -337,20 +337,31 @@ def side_measurements(kvp, workloads, torch, dev, K8, V8):
     t_smooth = _time_loop(torch, lambda: kvp.kvp_smooth_scores(sc.view(Ls * c["H"], c["T"]), c["W"], 7, "max", out=sm), 10)
     keep = idx.view(Ls, c["H"], k)
     t_gq = _time_loop(torch, lambda: kvp.kvp_quantize(Kc, qk, keep_idx=keep), 5)
+    # restore of the dropped+quantized plane: compact (k-slot pool) and at the original positions (T-token pool)
+    btk, nbk = workloads.make_block_table(k, 16, seed=0, device=dev)
+    btT, nbT = workloads.make_block_table(c["T"], 16, seed=0, device=dev)
+    pk = kvp.alloc_paged(Ls, k, c["H"], c["D"], btk, nbk, 16)
+    pT = kvp.alloc_paged(Ls, c["T"], c["H"], c["D"], btT, nbT, 16)
+    t_rc = _time_loop(torch, lambda: kvp.kvp_dequantize_paged(qk, pk), 5)
+    t_rs = _time_loop(torch, lambda: kvp.kvp_dequantize_paged_scatter(qk, keep, pT), 5)
+    restore_bytes = qk.nbytes() + Ls * k * c["H"] * c["D"] * 2
     M = c["G"] * c["W"]
     flops = 2 * 2.0 * Ls * c["H"] * M * c["T"] * c["D"]
     sel_bytes = Ls * c["H"] * (c["T"] + k) * 4
     gq_bytes = Ls * k * c["H"] * c["D"] * 2 + qk.nbytes() + idx.numel() * 4
     ops["llama3_70b_drop_int4"] = {
-        "workload": f"{Ls} of 80 layers x {c['H']} x {c['D']} x {c['T']}, G={c['G']}, W={c['W']}, keep {k}",
+        "workload": f"{Ls} x {c['H']} x {c['D']} x {c['T']}, G={c['G']}, W={c['W']}, keep {k}",
         "score_ms": round(t_score * 1e3, 3), "score_TFLOPs": round(flops / t_score / 1e12, 1),
         "score_frac_mfma": round(flops / t_score / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
         "select_us": round(t_sel * 1e6, 1), "select_GBs_alg": round(sel_bytes / t_sel / 1e9, 1),
         "select_frac_hbm": round(sel_bytes / t_sel / 1e9 / HBM_PEAK_GBS, 4),
         "smooth_k7_us": round(t_smooth * 1e6, 1), "smooth_GBs_alg": round(2 * sc.numel() * 4 / t_smooth / 1e9, 1),
         "gather_quantize_ms_per_plane": round(t_gq * 1e3, 3), "gather_quantize_GBs_alg": round(gq_bytes / t_gq / 1e9, 1),
+        "restore_compact_ms_per_plane": round(t_rc * 1e3, 3), "restore_compact_GBs_alg": round(restore_bytes / t_rc / 1e9, 1),
+        "restore_scatter_ms_per_plane": round(t_rs * 1e3, 3),
+        "restore_scatter_GBs_alg": round((restore_bytes + idx.numel() * 4) / t_rs / 1e9, 1),
         "pipeline_input_GBs": round(2 * Kc.numel() * 2 / (t_score + t_sel + 2 * t_gq) / 1e9, 1)}
-    del Kc, Vc, Qc, sc, sm, ws, idx, qk
+    del Kc, Vc, Qc, sc, sm, ws, idx, qk, pk, pT
     # --- long-context select: 112 rows of 131072 scores ---
     c = workloads.CONFIGS["long_context_int2"]
     rows = c["L"] * c["H"]
