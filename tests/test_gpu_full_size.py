@@ -91,6 +91,40 @@ def test_asymmetric_full_plane_sampled_rows():
     assert np.array_equal(torch_bits(pg.pool[li, blocks, ti % bs, hi]), od)
 
 
+@pytest.mark.parametrize("bits,group,asym", [(4, 32, False), (2, 128, True)])
+def test_per_channel_full_plane_sampled_groups(bits, group, asym):
+    # groups along tokens are independent of each other: a sampled (layer, token group, head) tile, quantized
+    # alone by the oracle, must reproduce the plane's codes, scales and minima for that tile
+    kvp = _kvp()
+    c = workloads.CONFIGS["llama3_8b_int4_paged"]
+    L, T, H, D, bs = c["L"], c["T"], c["H"], c["D"], c["bs"]
+    _say("full plane per-channel", (L, T, H, D), bits, group, asym)
+    K, _ = workloads.make_kv(L, T, H, D, seed=0, outlier_scale=c["outlier_scale"], device=DEV)
+    qp = kvp.alloc_qplane(L, T, H, D, bits, group, DEV, page=bs, asymmetric=asym, per_channel=True)
+    kvp.kvp_quantize(K, qp)
+    bt, nb = workloads.make_block_table(T, bs, seed=0, device=DEV)
+    pg = kvp.alloc_paged(L, T, H, D, bt, nb, bs)
+    kvp.kvp_dequantize_paged(qp, pg)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(4)
+    n_groups = T // group
+    picks = [(0, 0, 0), (L - 1, n_groups - 1, H - 1)] + [(int(rng.integers(L)), int(rng.integers(n_groups)), int(rng.integers(H)))
+                                                         for _ in range(30)]
+    for (l, g, h) in picks:
+        t0 = g * group
+        tile = torch_bits(K[l:l + 1, t0:t0 + group, h:h + 1])                 # [1][group][1][D]
+        oc, os_, om = oracle.quantize_channel(tile, bits, group, asym=asym)
+        assert np.array_equal(qp.codes[l, t0:t0 + group, h].cpu().numpy(), oc[0, :, 0])
+        assert np.array_equal(qp.scales[l, g, h].cpu().numpy().view(np.uint32), os_[0, 0, 0].view(np.uint32))
+        if asym:
+            assert np.array_equal(qp.mins[l, g, h].cpu().numpy().view(np.uint32), om[0, 0, 0].view(np.uint32))
+        ident = np.arange(group // bs, dtype=np.int32)
+        od = oracle.dequantize_paged_channel(oc, os_, om, bits, group, group, ident, len(ident), bs).reshape(group, D)
+        tt = torch.arange(t0, t0 + group, device=DEV)
+        got = torch_bits(pg.pool[l, bt.long()[tt // bs], tt % bs, h])
+        assert np.array_equal(got, od)
+
+
 def test_drop_then_quantize_70b_shape_sampled():
     kvp = _kvp()
     c = workloads.CONFIGS["llama3_70b_drop_int4"]
@@ -130,6 +164,22 @@ def test_drop_then_quantize_70b_shape_sampled():
     assert np.array_equal(qk.codes[li, si, hi].cpu().numpy(), oc[0, :, 0])
     assert np.array_equal(qk.scales[li, si, hi].cpu().numpy().view(np.uint32), os_[0, :, 0].view(np.uint32))
     assert not bool(qk.codes[:, k:].any()) and not bool(qk.scales[:, k:].any())   # padding slots
+    # restore at the original positions: sampled kept rows equal the oracle's dequantization of their slot,
+    # rows of dropped tokens keep the previous pool contents
+    bt, nb = workloads.make_block_table(T, 16, seed=0, device=DEV)
+    pool = torch.full((L, nb, 16, H, D), 7.0, dtype=torch.bfloat16, device=DEV)
+    pg = kvp.PagedKV(pool, bt, T)
+    kvp.kvp_dequantize_paged_scatter(qk, idx.view(L, H, k), pg)
+    torch.cuda.synchronize()
+    ident = np.arange((n + 15) // 16, dtype=np.int32)
+    od = oracle.dequantize_paged(oc, os_, c["bits"], c["group"], n, ident, len(ident), 16).reshape(-1, D)[:n]
+    blocks = bt.long()[ti.long() // 16]
+    assert np.array_equal(torch_bits(pool[li, blocks, ti.long() % 16, hi]), od)
+    kept = torch.zeros(L, H, T, dtype=torch.bool, device=DEV)
+    kept.scatter_(2, idx.view(L, H, k).long(), True)
+    tok_pool = pool[:, bt.long()].reshape(L, -1, H, D)[:, :T]                  # [L][T][H][D] in token order
+    dropped = ~kept.permute(0, 2, 1)                                           # [L][T][H]
+    assert bool((tok_pool[dropped] == 7.0).all())
 
 
 def test_long_context_select_full_rows():
