@@ -62,7 +62,7 @@ def main():
     args = parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (every box here has one); --gpus N with N > 1 is not "
-              "supported. The path shards by context / layer / KV head with no exchange (see DESIGN.md).",
+              "supported. The path shards by context / layer / KV head with no exchange between GPUs.",
               file=sys.stderr)
         sys.exit(2)
     ensure_built()
