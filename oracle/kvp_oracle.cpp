@@ -15,8 +15,8 @@
 // query and the earlier contexts, and drops those tokens with low
 // cross-attention scores").  The concrete arithmetic below is therefore a
 // stated reading (symmetric abs-max scaling, IEEE binary32 division,
-// round-half-to-even, lowest-index tie-break, keep count ceil(ratio*T)); the
-// readings are listed one by one in the design document of this repository.
+// round-half-to-even, lowest-index tie-break, keep count ceil(ratio*T)); each
+// reading is stated again at the function it governs.
 //
 // Parity status:
 //   oracle_quantize / oracle_dequantize_paged / oracle_select_topk: pinned by
@@ -24,6 +24,10 @@
 //     force (tests/test_oracle_*.py).
 //   oracle_quantize_asym / oracle_dequantize_paged_asym: pinned the same way (hand-exact
 //     examples, exact rational arithmetic, invariants).
+//   oracle_quantize_channel / oracle_dequantize_paged_channel: hand-exact examples, reduction to the
+//     per-token quantizers on a transposed tile, exact rational arithmetic, invariants.
+//   oracle_dequantize_paged_scatter: composition with the compact dequantizers plus a brute-force
+//     address check.  oracle_smooth_scores: library pooling, closed forms, brute force.
 //   oracle_score_keys (knorm, keydiff): pinned by closed forms (3-4-5 norms, identical / orthogonal /
 //     antipodal keys), scale invariance and a library float64 normalize + matmul.
 //   oracle_score_tokens / oracle_eval_configs: pinned by closed forms,
