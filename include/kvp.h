@@ -255,6 +255,8 @@ int64_t kvp_keep_count(double ratio, int64_t T);
 int32_t kvp_copy_bytes(void* dst, const void* src, size_t nbytes, void* stream);
 
 const char* kvp_strerror(int32_t code);
+/* 0x00MMmmpp.  1.3: kvp_qplane carries mins and group_axis; scatter restore, score smoothing and
+ * kvp_eval_configs_ex exist. */
 uint32_t kvp_version(void);
 
 #ifdef __cplusplus

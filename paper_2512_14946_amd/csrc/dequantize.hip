@@ -206,4 +206,5 @@ extern "C" const char* kvp_strerror(int32_t code) {
   }
 }
 
-extern "C" uint32_t kvp_version(void) { return 0x00010000u; }
+// major.minor.patch as 0x00MMmmpp; the minor number moves whenever a struct of the ABI gains a field
+extern "C" uint32_t kvp_version(void) { return 0x00010300u; }
