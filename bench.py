@@ -286,13 +286,31 @@ def side_measurements(kvp, workloads, torch, dev, K8, V8):
     t_same_d = _time_loop(torch, lambda: kvp.kvp_dequantize_paged(q1[0], p1[0]), 50, warm=5)
     t_rot_q = _time_loop(torch, rot_q, 3) / n_rot
     t_rot_d = _time_loop(torch, rot_d, 3) / n_rot
+    # the same 64 launches replayed from a HIP graph (the library neither allocates nor synchronizes,
+    # so a caller can capture it): what is left is the device-side launch cost
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        rot_q()
+        rot_d()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    gq, gd = torch.cuda.CUDAGraph(), torch.cuda.CUDAGraph()
+    with torch.cuda.graph(gq):
+        rot_q()
+    with torch.cuda.graph(gd):
+        rot_d()
+    t_graph_q = _time_loop(torch, gq.replay, 5) / n_rot
+    t_graph_d = _time_loop(torch, gd.replay, 5) / n_rot
     ops["single_layer_int8"] = {
         "workload": f"1x{c1['H']}x{c1['D']}x{c1['T']} plane (8 MiB), int8 g128; 'rotating' = {n_rot} independent copies in turn",
         "quantize_us_cache_resident": round(t_same_q * 1e6, 1), "dequantize_us_cache_resident": round(t_same_d * 1e6, 1),
         "quantize_us_rotating": round(t_rot_q * 1e6, 1), "dequantize_us_rotating": round(t_rot_d * 1e6, 1),
         "quantize_GBs_alg_rotating": round(alg1 / t_rot_q / 1e9, 1), "dequantize_GBs_alg_rotating": round(alg1 / t_rot_d / 1e9, 1),
+        "quantize_us_rotating_hip_graph": round(t_graph_q * 1e6, 1), "dequantize_us_rotating_hip_graph": round(t_graph_d * 1e6, 1),
+        "quantize_GBs_alg_hip_graph": round(alg1 / t_graph_q / 1e9, 1), "dequantize_GBs_alg_hip_graph": round(alg1 / t_graph_d / 1e9, 1),
         "note": "launch-bound: one call moves 16.3 MB (2 us at peak); times include the per-call launch path"}
-    del K1, q1, p1, views
+    del gq, gd, K1, q1, p1, views
     # --- long-context int2 config at its true shape (4 KV heads: 16 KiB pages, outlier channels x16) ---
     c5 = workloads.CONFIGS["long_context_int2"]
     K5, _ = workloads.make_kv(c5["L"], c5["T"], c5["H"], c5["D"], seed=0, outlier_scale=c5["outlier_scale"], device=dev)

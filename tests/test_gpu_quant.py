@@ -291,3 +291,45 @@ def test_asymmetric_scale_exact_for_many_ranges(bits):
     assert np.array_equal(qp.scales.cpu().numpy().view(np.uint32), os_.view(np.uint32))
     assert np.array_equal(qp.mins.cpu().numpy().view(np.uint32), om.view(np.uint32))
     assert np.array_equal(qp.codes.cpu().numpy(), oc)
+
+
+def test_hip_graph_replays_match_eager():
+    # the library neither allocates nor synchronizes, so its calls can be captured; every replay must give
+    # the eager result, with eager work and synchronizations between the replays
+    kvp = _kvp()
+    _say("hip graph replay")
+    L, T, H, D, bs = 2, 300, 8, 128, 16
+    K, V = workloads.make_kv(L, T, H, D, seed=77)
+    Kd, Vd = K.to(DEV), V.to(DEV)
+    qp = kvp.alloc_qplane(L, T, H, D, 4, 64, DEV)
+    bt, nb = workloads.make_block_table(T, bs, seed=2, device=DEV)
+    pg = kvp.alloc_paged(L, T, H, D, bt, nb, bs)
+    x = torch.empty_like(Kd)
+
+    def step():
+        kvp.kvp_quantize(x, qp)
+        kvp.kvp_dequantize_paged(qp, pg)
+
+    x.copy_(Kd)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()                                   # warm-up outside the capture
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        step()
+    for rep, src in enumerate([Kd, Vd, Kd, Vd]):
+        x.copy_(src)                             # eager work between the replays
+        qp.codes.fill_(0xEE)
+        pg.pool.fill_(float("nan"))
+        g.replay()
+        torch.cuda.synchronize()
+        got_codes, got_pool = qp.codes.clone(), pg.pool.clone()
+        step()                                   # the eager result for the same input
+        torch.cuda.synchronize()
+        assert torch.equal(got_codes, qp.codes), rep
+        assert torch.equal(got_pool.view(torch.int16), pg.pool.view(torch.int16)), rep
+    oc, _ = oracle.quantize(torch_bits(V), 4, 64, Tp=qp.Tp)
+    assert np.array_equal(qp.codes.cpu().numpy(), oc)
