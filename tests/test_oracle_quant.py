@@ -329,3 +329,28 @@ def test_asym_invariants_and_gain_over_symmetric(bits, group):
     cs, ss = oracle.quantize(x, bits, group)
     ys = bits_to_f32(oracle.dequantize_paged(cs, ss, bits, group, 64, bt, 4, 16).reshape(2, 64, 2, 128))
     assert np.square(ya - xf).sum() < np.square(ys - xf).sum()
+
+
+@pytest.mark.parametrize("bits,group", [(8, 128), (4, 64), (4, 32), (2, 32)])
+def test_numpy_float32_cross_check(bits, group):
+    # the same arithmetic with a library's IEEE binary32 division and round-half-even, symmetric and asymmetric
+    K, _ = workloads.make_kv(2, 64, 2, 128, seed=bits + group)
+    xb = torch_bits(K)
+    x = bits_to_f32(xb).reshape(-1, 128 // group, group)
+    qmax = np.float32((1 << (bits - 1)) - 1)
+    amax = np.abs(x).max(-1, keepdims=True)
+    scale = (amax / qmax).astype(np.float32)
+    with np.errstate(divide="ignore", invalid="ignore"):
+        q = np.where(scale > 0, np.rint((x / scale).astype(np.float32)), 0).astype(np.int32)
+    codes, scales = oracle.quantize(xb, bits, group)
+    assert np.array_equal(scales.reshape(-1, 128 // group), scale[..., 0])
+    assert np.array_equal(_unpack(codes, bits).reshape(x.shape), q)
+    levels = np.float32((1 << bits) - 1)
+    mn, mx = x.min(-1, keepdims=True), x.max(-1, keepdims=True)
+    sc = ((mx - mn).astype(np.float32) / levels).astype(np.float32)
+    with np.errstate(divide="ignore", invalid="ignore"):
+        qa = np.where(sc > 0, np.rint(((x - mn).astype(np.float32) / sc).astype(np.float32)), 0).astype(np.int32)
+    ca, sa, ma = oracle.quantize_asym(xb, bits, group)
+    assert np.array_equal(sa.reshape(-1, 128 // group), sc[..., 0])
+    assert np.array_equal(ma.reshape(-1, 128 // group), mn[..., 0])
+    assert np.array_equal(_unpack_unsigned(ca, bits).reshape(x.shape), qa)
