@@ -20,9 +20,9 @@ template <bool MAXPOOL>
 __global__ __launch_bounds__(kThreads) void smooth_kernel(const float* __restrict__ scores, int64_t row_stride, uint32_t T,
                                                           uint32_t P, int r, float* __restrict__ out, int64_t out_stride) {
   __shared__ float tile[kTile + kMaxKernel - 1];
-  const float* in = scores + static_cast<int64_t>(blockIdx.y) * row_stride;
-  float* o = out + static_cast<int64_t>(blockIdx.y) * out_stride;
-  const uint32_t t0 = blockIdx.x * kTile;
+  const float* in = scores + static_cast<int64_t>(blockIdx.x) * row_stride;   // x: row (up to 2^31 - 1), y: tile
+  float* o = out + static_cast<int64_t>(blockIdx.x) * out_stride;
+  const uint32_t t0 = blockIdx.y * kTile;
   const float neutral = MAXPOOL ? -INFINITY : 0.0f;
   const int span = kTile + 2 * r;
   for (int i = threadIdx.x; i < span; i += kThreads) {
@@ -56,7 +56,7 @@ extern "C" int32_t kvp_smooth_scores(const float* scores, int64_t n_rows, int64_
   if (!scores || !out) return KVP_ERR_NULL;
   if (n_rows < 0 || T <= 0 || T >= (1ll << 31) || row_stride < T || out_stride < T || window < 0 || window > T)
     return KVP_ERR_SHAPE;
-  if (n_rows > 65535) return KVP_ERR_SHAPE;
+  if (n_rows >= (1ll << 31) || ceil_div(T, kTile) > 65535) return KVP_ERR_SHAPE;
   if (kernel < 1 || kernel > kMaxKernel || kernel % 2 == 0) return KVP_ERR_UNSUPPORTED;
   if (mode != KVP_SMOOTH_AVG && mode != KVP_SMOOTH_MAX) return KVP_ERR_UNSUPPORTED;
   if ((reinterpret_cast<uintptr_t>(scores) & 3u) || (reinterpret_cast<uintptr_t>(out) & 3u)) return KVP_ERR_ALIGN;
@@ -68,7 +68,7 @@ extern "C" int32_t kvp_smooth_scores(const float* scores, int64_t n_rows, int64_
     const char* b1 = b0 + ((n_rows - 1) * out_stride + T) * 4;
     if (a0 < b1 && b0 < a1) return KVP_ERR_SHAPE;
   }
-  const dim3 grid(static_cast<unsigned>(ceil_div(T, kTile)), static_cast<unsigned>(n_rows));
+  const dim3 grid(static_cast<unsigned>(n_rows), static_cast<unsigned>(ceil_div(T, kTile)));
   const hipStream_t st = as_stream(stream);
   const uint32_t P = static_cast<uint32_t>(T - window);
   if (mode == KVP_SMOOTH_MAX)
