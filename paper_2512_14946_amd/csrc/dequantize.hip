@@ -10,6 +10,8 @@
 // scale, and stores 16 bytes.  y = (float)code * scale is one binary32 multiply, rounded to bf16
 // (nearest even) on the integer pattern, so the output is bit-identical to the definition.
 
+#include <type_traits>
+
 #include "kvp_common.h"
 #include "kvp_internal.h"
 #include "quant_device.h"
@@ -41,7 +43,11 @@ __global__ __launch_bounds__(kThreads) void dequantize_paged_kernel(const Dequan
   const float* mins = ASYM ? a.mins + src_row0 * NS : nullptr;
   uint16_t* dst = a.pool + static_cast<int64_t>(l) * a.pool_stride_l + blk * a.bs * a.H * kHeadDim;
 
-  for (uint32_t r0 = row_in_step; r0 < rows; r0 += kRowsPerStep * kUnroll) {
+  // One sweep: kUnroll rows per thread, all loads first.  FULL: every row of the sweep exists (the
+  // common case: a whole page of 16 tokens x 8 heads is exactly one sweep), so the code carries no
+  // per-row guards and no branches.
+  auto sweep = [&](auto full_tag, uint32_t r0) {
+    constexpr bool FULL = decltype(full_tag)::value;
     uint2 c[kUnroll];
     float s[kUnroll], m[kUnroll];
 #pragma unroll
@@ -50,7 +56,7 @@ __global__ __launch_bounds__(kThreads) void dequantize_paged_kernel(const Dequan
       c[u] = make_uint2(0, 0);
       s[u] = 0.0f;
       m[u] = 0.0f;
-      if (r < rows) {
+      if (FULL || r < rows) {
         if constexpr (ASYM) m[u] = __builtin_nontemporal_load(mins + static_cast<int64_t>(r) * NS + lane_in_row / LANES_PER_GROUP);
         c[u] = load_codes<BITS>(codes + static_cast<int64_t>(r) * CB, lane_in_row);
         s[u] = __builtin_nontemporal_load(scales + static_cast<int64_t>(r) * NS + lane_in_row / LANES_PER_GROUP);
@@ -59,7 +65,7 @@ __global__ __launch_bounds__(kThreads) void dequantize_paged_kernel(const Dequan
 #pragma unroll
     for (int u = 0; u < kUnroll; ++u) {
       const uint32_t r = r0 + u * kRowsPerStep;
-      if (r >= rows) continue;
+      if (!FULL && r >= rows) continue;
       uint32_t w[4];
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
@@ -74,6 +80,11 @@ __global__ __launch_bounds__(kThreads) void dequantize_paged_kernel(const Dequan
       uint16_t* out_row = SCATTER ? scatter_row(a, l, t0, r) : dst + static_cast<int64_t>(r) * kHeadDim;
       store_stream16(out_row + lane_in_row * 8, make_uint4(w[0], w[1], w[2], w[3]));
     }
+  };
+  if (rows == kRowsPerStep * kUnroll) {
+    sweep(std::true_type{}, row_in_step);
+  } else {
+    for (uint32_t r0 = row_in_step; r0 < rows; r0 += kRowsPerStep * kUnroll) sweep(std::false_type{}, r0);
   }
 }
 
