@@ -67,6 +67,26 @@ def test_validation_rejects_before_any_launch(lib):
     lib.kvp_copy_bytes.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
     assert lib.kvp_copy_bytes(None, None, 16, None) == -1
     assert lib.kvp_copy_bytes(16, 32, 8, None) == -2
+    lib.kvp_dequantize_paged_scatter.restype = ctypes.c_int32
+    lib.kvp_dequantize_paged_scatter.argtypes = [ctypes.c_void_p] * 4
+    assert lib.kvp_dequantize_paged_scatter(None, None, None, None) == -1
+    lib.kvp_smooth_scores.restype = ctypes.c_int32
+    lib.kvp_smooth_scores.argtypes = [ctypes.c_void_p] + [ctypes.c_int64] * 4 + [ctypes.c_int32] * 2 + \
+        [ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p]
+    assert lib.kvp_smooth_scores(None, 1, 8, 8, 0, 3, 0, None, 8, None) == -1
+    assert lib.kvp_smooth_scores(256, 1, 8, 8, 0, 4, 0, 4096, 8, None) == -4      # even kernel
+    assert lib.kvp_smooth_scores(256, 1, 8, 8, 0, 3, 7, 4096, 8, None) == -4      # unknown mode
+    assert lib.kvp_smooth_scores(256, 1, 8, 8, 9, 3, 0, 4096, 8, None) == -3      # window longer than the row
+    assert lib.kvp_smooth_scores(256, 2, 8, 8, 0, 3, 0, 256 + 32, 8, None) == -3  # overlapping rows
+    assert lib.kvp_smooth_scores(256, 0, 8, 8, 0, 3, 0, 4096, 8, None) == 0       # nothing to do
+    lib.kvp_eval_configs_ex.restype = ctypes.c_int32
+    lib.kvp_eval_configs_ex.argtypes = [ctypes.c_void_p] * 4 + [ctypes.c_int32] + [ctypes.c_void_p] * 3 + \
+        [ctypes.c_size_t, ctypes.c_uint32, ctypes.c_void_p]
+    assert lib.kvp_eval_configs_ex(None, None, None, None, 1, None, None, None, 0, 2, None) == -4   # unknown flag
+    assert lib.kvp_eval_configs_ex(None, None, None, None, 1, None, None, None, 0, 1, None) == -1
+    lib.kvp_score_keys.restype = ctypes.c_int32
+    lib.kvp_score_keys.argtypes = [ctypes.c_void_p, ctypes.c_int32] + [ctypes.c_void_p] * 2 + [ctypes.c_size_t, ctypes.c_void_p]
+    assert lib.kvp_score_keys(None, 0, None, None, 0, None) == -1
 
 
 def test_binding_refuses_cpu_tensors():
