@@ -187,47 +187,72 @@ __global__ __launch_bounds__((PASS_B ? kWavesB : kWavesA) * kWave, 2) void score
     }
   };
 
-  // One 32-key tile against all query tiles, two tiles in flight (A / B buffers).
+  // The LDS reads of a query tile's operands are issued one whole pipeline step before the MFMAs that
+  // use them; a scheduling barrier keeps the compiler from sinking them back next to their use (where
+  // every MFMA would wait out the LDS latency on its own).
+  auto pin = [&]() { __builtin_amdgcn_sched_barrier(0); };
+
+  // One 32-key tile against all query tiles as a software pipeline over the query tiles:
+  //   step n:  LDS operand reads of tile n+2, then  MFMAs of tile n+1  |  vector-ALU work of tile n.
   auto key_tile = [&](auto masked_tag, const uint4 kop[8], int tk0) {
     bf16x8 qop_a[8], qop_b[8];
     floatx16 acc_a, acc_b;
     float col = 0.0f, dummy_m = 0.0f, dummy_z = 0.0f;  // pass B: this lane's key column
+    auto finish_column = [&]() {
+      if constexpr (PASS_B) {
+        col += __shfl_xor(col, 32, 64);
+        const int t = tk0 + lane;
+        if (lane < 32 && t < a.T)
+          a.scores[static_cast<int64_t>(lh) * a.T + t] = (a.force_window && t >= win0) ? INFINITY : col;
+      }
+    };
     q_operand(0, qop_a);
     acc_a = mfma_tile(kop, qop_a);
-    if constexpr (!PASS_B) {
-      // the per-tile running statistics need static register indices: fully unrolled
-#pragma unroll
-      for (int qt = 0; qt < NQT; qt += 2) {
-        if (qt + 1 < NQT) {
-          q_operand(qt + 1, qop_b);
-          acc_b = mfma_tile(kop, qop_b);
-        }
-        consume(masked_tag, acc_a, qt, tk0, col, run_m[qt], run_z[qt]);
-        if (qt + 2 < NQT) {
-          q_operand(qt + 2, qop_a);
-          acc_a = mfma_tile(kop, qop_a);
-        }
-        if (qt + 1 < NQT) consume(masked_tag, acc_b, qt + 1, tk0, col, run_m[(qt + 1) % NQT], run_z[(qt + 1) % NQT]);
-      }
+    if constexpr (NQT == 1) {
+      consume(masked_tag, acc_a, 0, tk0, col, run_m[0], run_z[0]);
+      finish_column();
     } else {
-      // no per-tile state: a rolled loop keeps the register footprint independent of the tile count
-#pragma unroll 1
-      for (int qt = 0; qt < NQT; qt += 2) {
-        if (qt + 1 < NQT) {
-          q_operand(qt + 1, qop_b);
-          acc_b = mfma_tile(kop, qop_b);
-        }
-        consume(masked_tag, acc_a, qt, tk0, col, dummy_m, dummy_z);
-        if (qt + 2 < NQT) {
+      q_operand(1, qop_b);
+      if constexpr (!PASS_B) {
+        // the per-tile running statistics need static register indices: fully unrolled
+#pragma unroll
+        for (int qt = 0; qt + 2 < NQT; qt += 2) {
           q_operand(qt + 2, qop_a);
+          pin();
+          acc_b = mfma_tile(kop, qop_b);
+          consume(masked_tag, acc_a, qt, tk0, col, run_m[qt], run_z[qt]);
+          pin();
+          q_operand(qt + 3, qop_b);
+          pin();
           acc_a = mfma_tile(kop, qop_a);
+          consume(masked_tag, acc_b, qt + 1, tk0, col, run_m[qt + 1], run_z[qt + 1]);
+          pin();
         }
-        if (qt + 1 < NQT) consume(masked_tag, acc_b, qt + 1, tk0, col, dummy_m, dummy_z);
+        acc_b = mfma_tile(kop, qop_b);
+        consume(masked_tag, acc_a, NQT - 2, tk0, col, run_m[NQT - 2], run_z[NQT - 2]);
+        pin();
+        consume(masked_tag, acc_b, NQT - 1, tk0, col, run_m[NQT - 1], run_z[NQT - 1]);
+      } else {
+        // no per-tile state: a rolled loop keeps the register footprint independent of the tile count
+#pragma unroll 1
+        for (int qt = 0; qt + 2 < NQT; qt += 2) {
+          q_operand(qt + 2, qop_a);
+          pin();
+          acc_b = mfma_tile(kop, qop_b);
+          consume(masked_tag, acc_a, qt, tk0, col, dummy_m, dummy_z);
+          pin();
+          q_operand(qt + 3, qop_b);
+          pin();
+          acc_a = mfma_tile(kop, qop_a);
+          consume(masked_tag, acc_b, qt + 1, tk0, col, dummy_m, dummy_z);
+          pin();
+        }
+        acc_b = mfma_tile(kop, qop_b);
+        consume(masked_tag, acc_a, NQT - 2, tk0, col, dummy_m, dummy_z);
+        pin();
+        consume(masked_tag, acc_b, NQT - 1, tk0, col, dummy_m, dummy_z);
+        finish_column();
       }
-      col += __shfl_xor(col, 32, 64);
-      const int t = tk0 + lane;
-      if (lane < 32 && t < a.T)
-        a.scores[static_cast<int64_t>(lh) * a.T + t] = (a.force_window && t >= win0) ? INFINITY : col;
     }
   };
 
