@@ -404,8 +404,9 @@ def side_measurements(kvp, workloads, torch, dev, K8, V8):
     t_ev = _time_loop(torch, lambda: kvp.kvp_eval_configs(Qe, Ke, Ve, cfgs, loss=loss, ws=ws), 2)
     t_ev_mx = _time_loop(torch, lambda: kvp.kvp_eval_configs(Qe, Ke, Ve, cfgs, loss=loss, ws=ws, pv_matrix_cores=True), 2)
     M = c["G"] * c["W"]
-    # work actually done: the reference pass plus one stream per codec, each over the largest keep-set
-    tokens = (1 + len(variants)) * max(ks)
+    # work actually done: one stream per codec, each over the largest keep-set (here all T tokens); the
+    # 16-bit stream doubles as the reference
+    tokens = len(variants) * max(ks)
     pv_flops = 2.0 * c["L"] * c["H"] * M * c["D"] * tokens
     ops["utility_sweep"] = {"workload": f"1 of {c['n_ctx']} contexts: {c['L']}x{c['H']}x{c['D']}x{c['T']}, {len(cfgs)} configs",
                             "eval_ms_per_context": round(t_ev * 1e3, 2), "configs_per_s": round(len(cfgs) / t_ev, 1),

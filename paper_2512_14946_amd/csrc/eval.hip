@@ -72,11 +72,13 @@ struct EvalArgs {
   int32_t n_streams, n_cfgs, n_levels;
   int32_t level_k[kMaxLevels];           // ascending
   const int32_t* level_idx[kMaxLevels];  // [L*Hkv][k] ascending keep list, or null when k == T
-  StreamDesc streams[kMaxCfgs];
+  StreamDesc streams[kMaxCfgs + 1];      // + a hidden 16-bit stream when no configuration asks for one
+  int32_t ref_stream;                    // the 16-bit stream: it walks all T tokens and doubles as the reference
   uint8_t cfg_stream[kMaxCfgs], cfg_level[kMaxCfgs];
   uint8_t* shell;   // [L*Hkv][T] scratch: index of the first keep level that holds the token
   int32_t* order;   // [L*Hkv][T] tokens ordered by shell, ascending inside a shell
-  float* o_full;    // [L*Hkv][RB][128][128]
+  float* o_levels;  // [L*Hkv][RB][n_streams][n_levels + 1][128 x 128]: normalized output of a stream at each level
+                    // (slot n_levels: the reference's state after all T tokens)
   float* den_part;  // [L*Hkv][RB]
   float* num_part;  // [L*Hkv][RB][n_streams][n_levels]
   double* layer_part;  // [L][n_cfgs][2] scratch of the final reduction
@@ -220,9 +222,10 @@ __device__ __forceinline__ void stage_v_transposed(uint16_t* vt_s, uint4 vp, int
   *reinterpret_cast<uint2*>(vt_s + vt_row(part * 8 + 2 * j + 1) * kVtPitch + col) = odd;
 }
 
-// REFERENCE: stream = (16 bits, all tokens); writes O_full and the denominator.
+// One launch covers every stream; the 16-bit stream also walks the tokens no keep level holds and so ends
+// as the reference O_full.  Outputs are compared afterwards (compare_kernel).
 // PV_MFMA: the P.V product on the matrix cores (two-term bf16 split of P) instead of the vector ALU.
-template <bool REFERENCE, bool PV_MFMA>
+template <bool PV_MFMA>
 __global__ __launch_bounds__(kThreads, KVP_EVAL_WAVES_PER_SIMD) void attention_kernel(const EvalArgs a) {
   __shared__ __attribute__((aligned(16))) uint16_t k_s[kTile * kPitch];
   // V-hat: transposed bf16 for the matrix cores (see v_operand), or fp32 [token][channel] for the vector ALU
@@ -238,11 +241,8 @@ __global__ __launch_bounds__(kThreads, KVP_EVAL_WAVES_PER_SIMD) void attention_k
   const int half = lane >> 5;
   const int rb = blockIdx.x, lh = blockIdx.y;
   const int l = lh / a.Hkv, h = lh - l * a.Hkv;
-  int bits = 16, group = 128;
-  if constexpr (!REFERENCE) {
-    bits = a.streams[blockIdx.z].bits;
-    group = a.streams[blockIdx.z].group;
-  }
+  const int bits = a.streams[blockIdx.z].bits, group = a.streams[blockIdx.z].group;
+  const bool is_ref = static_cast<int>(blockIdx.z) == a.ref_stream;
   const int32_t* order = a.order + static_cast<int64_t>(lh) * a.T;
   const uint16_t* kbase = a.k + static_cast<int64_t>(l) * a.k_sl + static_cast<int64_t>(h) * a.k_sh;
   const uint16_t* vbase = a.v + static_cast<int64_t>(l) * a.v_sl + static_cast<int64_t>(h) * a.v_sh;
@@ -273,16 +273,14 @@ __global__ __launch_bounds__(kThreads, KVP_EVAL_WAVES_PER_SIMD) void attention_k
 #pragma unroll
   for (int i = 0; i < 64; ++i) o[i] = 0.0f;
   const int ty = tid >> 4, tx = tid & 15;
-  // reference output of this block; each thread's 64 values are contiguous (same thread, same layout in
-  // the reference pass and in the streams)
-  float4* cell = reinterpret_cast<float4*>(a.o_full + (static_cast<int64_t>(lh) * a.RB + rb) * kRowsPerBlock * kHeadDim +
-                                           tid * 64);
+  // this block's output slots; each thread's 64 values of a level are contiguous
+  float* levels_out = a.o_levels + (((static_cast<int64_t>(lh) * a.RB + rb) * a.n_streams + blockIdx.z) * (a.n_levels + 1)) *
+                                       (kRowsPerBlock * kHeadDim) + tid * 64;
 
   // segments end at the keep levels (tiles never straddle a level boundary, so the state at a
-  // boundary is exactly that level's attention).  The reference walks the same tiles, plus the
-  // tokens no level keeps, and only looks at its state at the very end: a 16-bit stream is then
-  // bit-identical to it wherever the two cover the same tokens.
-  const int n_seg = a.n_levels + ((REFERENCE && a.level_k[a.n_levels - 1] < a.T) ? 1 : 0);
+  // boundary is exactly that level's attention).  The 16-bit stream also walks the tokens no level
+  // keeps (one more segment), which makes its final state the reference.
+  const int n_seg = a.n_levels + ((is_ref && a.level_k[a.n_levels - 1] < a.T) ? 1 : 0);
   auto seg_end_of = [&](int sg) { return sg < a.n_levels ? a.level_k[sg] : a.T; };
 
   // Tile cursor: tile = positions [pos, min(pos + 32, end)) of segment seg.  Global loads run ahead of
@@ -453,54 +451,79 @@ __global__ __launch_bounds__(kThreads, KVP_EVAL_WAVES_PER_SIMD) void attention_k
       }
     }
     if (cur.seg == seg) continue;                      // more tiles in this segment
-    if (REFERENCE && seg != n_seg - 1) continue;
 
-    // ---- end of a segment: normalize a copy, then store (reference) or compare with the reference ----
+    // ---- end of a segment: store the normalized output of this level ----
     float inv[8];      // 1 / row sum of the rows this thread's accumulators belong to
-    bool live[8];
     if constexpr (PV_MFMA) {
       const float one = 1.0f / (run_z + __shfl_xor(run_z, 32, 64));
 #pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        inv[i] = one;
-        live[i] = qrow < a.M;
-      }
+      for (int i = 0; i < 8; ++i) inv[i] = one;
     } else {
       const float z = run_z + __shfl_xor(run_z, 32, 64);
       __syncthreads();
       if (lane < 32) z_s[wave * 32 + lane] = z;
       __syncthreads();
 #pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        const int rloc = (i < 4) ? 4 * ty + i : 64 + 4 * ty + (i - 4);
-        inv[i] = 1.0f / z_s[rloc];
-        live[i] = rb * kRowsPerBlock + rloc < a.M;
-      }
+      for (int i = 0; i < 8; ++i) inv[i] = 1.0f / z_s[(i < 4) ? 4 * ty + i : 64 + 4 * ty + (i - 4)];
     }
-    float sq = 0.0f;
+    float4* cell = reinterpret_cast<float4*>(levels_out + static_cast<int64_t>(seg) * (kRowsPerBlock * kHeadDim));
 #pragma unroll
     for (int i = 0; i < 8; ++i)       // accumulators 8 i .. 8 i + 7 share a row in the vector-ALU layout
 #pragma unroll
       for (int jh = 0; jh < 2; ++jh) {
         const int e = 8 * i + 4 * jh;
-        const float4 val = make_float4(o[e] * inv[i], o[e + 1] * inv[i], o[e + 2] * inv[i], o[e + 3] * inv[i]);
-        if constexpr (REFERENCE) {
-          cell[e >> 2] = val;
-          if (live[i]) sq += val.x * val.x + val.y * val.y + val.z * val.z + val.w * val.w;
-        } else {
-          const float4 ref = cell[e >> 2];
-          const float dx = val.x - ref.x, dy = val.y - ref.y, dz = val.z - ref.z, dw = val.w - ref.w;
-          if (live[i]) sq += dx * dx + dy * dy + dz * dz + dw * dw;
-        }
+        cell[e >> 2] = make_float4(o[e] * inv[i], o[e + 1] * inv[i], o[e + 2] * inv[i], o[e + 3] * inv[i]);
       }
-    const float total = block_sum(sq, red_s);
-    if (tid == 0) {
-      if constexpr (REFERENCE) {
-        a.den_part[static_cast<int64_t>(lh) * a.RB + rb] = total;
-      } else {
-        a.num_part[((static_cast<int64_t>(lh) * a.RB + rb) * a.n_streams + blockIdx.z) * a.n_levels + seg] = total;
-      }
+    // the reference state is the last one the 16-bit stream reaches; keep it in the extra slot as well
+    if (is_ref && seg == n_seg - 1 && seg != a.n_levels) {
+      float4* last = reinterpret_cast<float4*>(levels_out + static_cast<int64_t>(a.n_levels) * (kRowsPerBlock * kHeadDim));
+#pragma unroll
+      for (int q4 = 0; q4 < 16; ++q4) last[q4] = cell[q4];
     }
+  }
+}
+
+// Squared distances between every stored level of every stream and the reference, and the reference's own
+// squared norm: block (row block, layer x head, stream), thread layout as in attention_kernel.
+template <bool PV_MFMA>
+__global__ __launch_bounds__(kThreads) void compare_kernel(const EvalArgs a) {
+  __shared__ float red_s[4];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int rb = blockIdx.x, lh = blockIdx.y, st = blockIdx.z;
+  const int64_t cellrow = static_cast<int64_t>(lh) * a.RB + rb;
+  const int64_t per_level = kRowsPerBlock * kHeadDim;
+  const float* ref = a.o_levels + ((cellrow * a.n_streams + a.ref_stream) * (a.n_levels + 1) + a.n_levels) * per_level + tid * 64;
+  // which of this thread's 64 values belong to live query rows
+  bool live[8];
+  const int ty = tid >> 4;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    const int rloc = PV_MFMA ? wave * 32 + (lane & 31) : ((i < 4) ? 4 * ty + i : 64 + 4 * ty + (i - 4));
+    live[i] = rb * kRowsPerBlock + rloc < a.M;
+  }
+  float4 r[16];
+#pragma unroll
+  for (int q4 = 0; q4 < 16; ++q4) r[q4] = reinterpret_cast<const float4*>(ref)[q4];
+  if (st == a.ref_stream) {
+    float sq = 0.0f;
+#pragma unroll
+    for (int q4 = 0; q4 < 16; ++q4)
+      if (live[q4 >> 1]) sq += r[q4].x * r[q4].x + r[q4].y * r[q4].y + r[q4].z * r[q4].z + r[q4].w * r[q4].w;
+    const float total = block_sum(sq, red_s);
+    if (tid == 0) a.den_part[cellrow] = total;
+  }
+  for (int lev = 0; lev < a.n_levels; ++lev) {
+    const float4* val = reinterpret_cast<const float4*>(a.o_levels + ((cellrow * a.n_streams + st) * (a.n_levels + 1) + lev) * per_level +
+                                                        tid * 64);
+    float sq = 0.0f;
+#pragma unroll
+    for (int q4 = 0; q4 < 16; ++q4) {
+      const float4 v = val[q4];
+      const float dx = v.x - r[q4].x, dy = v.y - r[q4].y, dz = v.z - r[q4].z, dw = v.w - r[q4].w;
+      if (live[q4 >> 1]) sq += dx * dx + dy * dy + dz * dz + dw * dw;
+    }
+    const float total = block_sum(sq, red_s);
+    if (tid == 0) a.num_part[(cellrow * a.n_streams + st) * a.n_levels + lev] = total;
   }
 }
 
@@ -542,7 +565,7 @@ size_t align256(size_t n) { return (n + 255) / 256 * 256; }
 
 struct EvalPlan {
   int64_t LH, M, RB;
-  size_t score_ws, scores, idx, shell, order, o_full, den, num, layer, total;
+  size_t score_ws, scores, idx, shell, order, o_levels, den, num, layer, total;
 };
 
 EvalPlan make_plan(int64_t L, int64_t Hkv, int64_t Hq, int64_t W, int64_t T, int32_t n_cfgs) {
@@ -557,11 +580,12 @@ EvalPlan make_plan(int64_t L, int64_t Hkv, int64_t Hq, int64_t W, int64_t T, int
   p.idx = align256(static_cast<size_t>(levels) * p.LH * T * sizeof(int32_t));
   p.shell = align256(static_cast<size_t>(p.LH) * T);
   p.order = align256(static_cast<size_t>(p.LH) * T * sizeof(int32_t));
-  p.o_full = align256(static_cast<size_t>(p.LH) * p.RB * kRowsPerBlock * kHeadDim * sizeof(float));
+  // every configuration may bring its own stream, plus the hidden 16-bit one
+  p.o_levels = align256(static_cast<size_t>(p.LH) * p.RB * (cfgs + 1) * (levels + 1) * kRowsPerBlock * kHeadDim * sizeof(float));
   p.den = align256(static_cast<size_t>(p.LH) * p.RB * sizeof(float));
-  p.num = align256(static_cast<size_t>(p.LH) * p.RB * cfgs * levels * sizeof(float));
+  p.num = align256(static_cast<size_t>(p.LH) * p.RB * (cfgs + 1) * levels * sizeof(float));
   p.layer = align256(static_cast<size_t>(L) * cfgs * 2 * sizeof(double));
-  p.total = p.score_ws + p.scores + p.idx + p.shell + p.order + p.o_full + p.den + p.num + p.layer;
+  p.total = p.score_ws + p.scores + p.idx + p.shell + p.order + p.o_levels + p.den + p.num + p.layer;
   return p;
 }
 
@@ -623,6 +647,27 @@ extern "C" int32_t kvp_eval_configs_ex(const kvp_view* q_win, const kvp_view* k,
     a.cfg_stream[c] = static_cast<uint8_t>(s);
   }
 
+  a.ref_stream = -1;
+  for (int j = 0; j < a.n_streams; ++j)
+    if (a.streams[j].bits == 16) a.ref_stream = j;
+  if (a.ref_stream < 0) {
+    a.ref_stream = a.n_streams++;
+    a.streams[a.ref_stream] = StreamDesc{16, 128};
+  }
+  // the reference stream walks the most tokens: give it the lowest block indices so that its blocks start first
+  if (a.ref_stream != 0) {
+    const StreamDesc first = a.streams[0];
+    a.streams[0] = a.streams[a.ref_stream];
+    a.streams[a.ref_stream] = first;
+    for (int32_t c = 0; c < n_cfgs; ++c) {
+      if (a.cfg_stream[c] == 0)
+        a.cfg_stream[c] = static_cast<uint8_t>(a.ref_stream);
+      else if (a.cfg_stream[c] == a.ref_stream)
+        a.cfg_stream[c] = 0;
+    }
+    a.ref_stream = 0;
+  }
+
   const EvalPlan p = make_plan(L, Hkv, Hq, W, T, n_cfgs);
   if (!ws || ws_bytes < p.total || (reinterpret_cast<uintptr_t>(ws) & 15u)) return KVP_ERR_WORKSPACE;
   char* cursor = static_cast<char*>(ws);
@@ -632,7 +677,7 @@ extern "C" int32_t kvp_eval_configs_ex(const kvp_view* q_win, const kvp_view* k,
   int32_t* idx = reinterpret_cast<int32_t*>(take(p.idx));
   a.shell = reinterpret_cast<uint8_t*>(take(p.shell));
   a.order = reinterpret_cast<int32_t*>(take(p.order));
-  a.o_full = reinterpret_cast<float*>(take(p.o_full));
+  a.o_levels = reinterpret_cast<float*>(take(p.o_levels));
   a.den_part = reinterpret_cast<float*>(take(p.den));
   a.num_part = reinterpret_cast<float*>(take(p.num));
   a.layer_part = reinterpret_cast<double*>(take(p.layer));
@@ -664,14 +709,13 @@ extern "C" int32_t kvp_eval_configs_ex(const kvp_view* q_win, const kvp_view* k,
     }
   }
   build_order_kernel<<<dim3(static_cast<unsigned>(p.LH)), kOrderThreads, 0, st>>>(a);
-  const dim3 grid_ref(static_cast<unsigned>(p.RB), static_cast<unsigned>(p.LH), 1);
-  const dim3 grid_streams(static_cast<unsigned>(p.RB), static_cast<unsigned>(p.LH), static_cast<unsigned>(a.n_streams));
+  const dim3 grid(static_cast<unsigned>(p.RB), static_cast<unsigned>(p.LH), static_cast<unsigned>(a.n_streams));
   if (flags & KVP_EVAL_PV_MATRIX_CORES) {
-    attention_kernel<true, true><<<grid_ref, kThreads, 0, st>>>(a);
-    attention_kernel<false, true><<<grid_streams, kThreads, 0, st>>>(a);
+    attention_kernel<true><<<grid, kThreads, 0, st>>>(a);
+    compare_kernel<true><<<grid, kThreads, 0, st>>>(a);
   } else {
-    attention_kernel<true, false><<<grid_ref, kThreads, 0, st>>>(a);
-    attention_kernel<false, false><<<grid_streams, kThreads, 0, st>>>(a);
+    attention_kernel<false><<<grid, kThreads, 0, st>>>(a);
+    compare_kernel<false><<<grid, kThreads, 0, st>>>(a);
   }
   finish_kernel<<<1, kFinishThreads, 0, st>>>(a);
   return launch_status();
