@@ -1,7 +1,7 @@
 // kvp_select_topk: per-row top-k keep-set by radix select (the paper's token dropping keeps the
 // tokens with the highest attention scores: Evaluation, Baselines, snapkv / IMPRESS "top X%").
 //
-// One 1024-thread block owns one row.  Scores are mapped to order-preserving unsigned keys; four
+// One block owns one row.  Scores are mapped to order-preserving unsigned keys; four
 // most-significant-digit-first passes over 8-bit digits find the key tau of the k-th largest score
 // and how many elements equal to tau belong to the keep-set.  Histograms live in LDS, replicated
 // 32 times and interleaved so that the 32 lanes of a half-wave always hit 32 different banks (token
@@ -10,23 +10,30 @@
 // earlier elements above tau) + min(number of earlier elements equal to tau, quota), so ties at
 // the threshold go to the lowest indices.  Integer compares only: the result is exact.
 //
-// Rows of up to 16384 scores are read from HBM exactly once and stay in registers (16 keys per
-// thread) through all passes.  Longer rows are processed in 16384-element spans that are re-read
-// (from L2 after the first pass) with the next span's loads issued before the current span is
-// consumed.  Every wave redoes the 256-bin digit search itself, so a pass costs two block barriers.
+// Rows of up to 16384 scores are read from HBM exactly once and stay in registers through all
+// passes: 16 keys per thread in a 1024-thread block, or 32 keys per thread in a 512-thread block
+// when there are more rows than the chip holds wide blocks (the work is bound by vector-ALU
+// instruction issue, about 60 per key, so what counts then is rows in flight per CU).  Longer rows
+// are processed in 16384-element spans that are re-read (from L2 after the first pass) with the
+// next span's loads issued before the current span is consumed.  Every wave redoes the 256-bin
+// digit search and the scan of the wave totals itself, so a pass costs two block barriers.
 
 #include "kvp_internal.h"
 
 namespace kvp {
 namespace {
 
-constexpr int kThreads = 1024;
-constexpr int kWaves = kThreads / kWave;
 constexpr int kCopies = 32;
 constexpr int kBins = 256;
-constexpr int kItems = 4;                           // float4 items per thread per span
-constexpr int kChunk = kThreads * 4;                // elements covered by one item of all threads
-constexpr int kSpan = kChunk * kItems;              // 16384 elements
+constexpr int kSpan = 16384;                        // elements a block holds in registers at a time
+
+// Block shapes: THREADS threads hold a span as ITEMS float4 items each.
+template <int THREADS>
+struct Shape {
+  static constexpr int kWaves = THREADS / kWave;
+  static constexpr int kChunk = THREADS * 4;        // elements covered by one item of all threads
+  static constexpr int kItems = kSpan / kChunk;     // 4 (1024 threads) or 8 (512 threads)
+};
 
 // IEEE order -> unsigned order; -0.0 is folded onto +0.0 so that they tie, as with operator>.
 // Key 0 would be a negative NaN (out of contract): it marks slots beyond the end of the row and
@@ -37,15 +44,18 @@ __device__ __forceinline__ uint32_t to_key(float f) {
   return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
 }
 
+template <int ITEMS>
 struct Span {
-  uint32_t key[kItems][4];
+  uint32_t key[ITEMS][4];
 };
 
-// Element index of (item c, thread tid, lane element e) inside a span: c * 4096 + tid * 4 + e.
-__device__ __forceinline__ void load_span(const float* row, int64_t base, int64_t T, bool vec, Span& s) {
+// Element index of (item c, thread tid, lane element e) inside a span: c * kChunk + tid * 4 + e.
+template <int THREADS>
+__device__ __forceinline__ void load_span(const float* row, int64_t base, int64_t T, bool vec,
+                                          Span<Shape<THREADS>::kItems>& s) {
 #pragma unroll
-  for (int c = 0; c < kItems; ++c) {
-    const int64_t i = base + c * kChunk + static_cast<int64_t>(threadIdx.x) * 4;
+  for (int c = 0; c < Shape<THREADS>::kItems; ++c) {
+    const int64_t i = base + c * Shape<THREADS>::kChunk + static_cast<int64_t>(threadIdx.x) * 4;
     if (vec && i + 4 <= T) {
       const float4 v = *reinterpret_cast<const float4*>(row + i);
       s.key[c][0] = to_key(v.x); s.key[c][1] = to_key(v.y); s.key[c][2] = to_key(v.z); s.key[c][3] = to_key(v.w);
@@ -56,10 +66,12 @@ __device__ __forceinline__ void load_span(const float* row, int64_t base, int64_
   }
 }
 
-__device__ __forceinline__ void histogram_span(const Span& s, uint32_t mask, uint32_t prefix, int shift, uint32_t* hist) {
+template <int ITEMS>
+__device__ __forceinline__ void histogram_span(const Span<ITEMS>& s, uint32_t mask, uint32_t prefix, int shift,
+                                               uint32_t* hist) {
   const int copy = threadIdx.x & (kCopies - 1);
 #pragma unroll
-  for (int c = 0; c < kItems; ++c)
+  for (int c = 0; c < ITEMS; ++c)
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
       const uint32_t key = s.key[c][e];
@@ -85,26 +97,30 @@ __device__ __forceinline__ uint32_t wave_inclusive_scan(uint32_t v) {
   return t;
 }
 
-// RESIDENT: T <= kSpan, the whole row lives in registers.
-template <bool RESIDENT>
-__global__ __launch_bounds__(kThreads, RESIDENT ? 8 : 4) void select_topk_kernel(const float* __restrict__ scores,
-                                                                                 int64_t T, int64_t row_stride,
-                                                                                 int64_t k,
-                                                                                 int32_t* __restrict__ idx_out) {
+// RESIDENT: T <= kSpan, the whole row lives in registers (8 waves per SIMD: two 1024-thread or four
+// 512-thread blocks per CU).
+template <int THREADS, bool RESIDENT>
+__global__ __launch_bounds__(THREADS, RESIDENT ? 8 : 4) void select_topk_kernel(const float* __restrict__ scores,
+                                                                                int64_t T, int64_t row_stride,
+                                                                                int64_t k,
+                                                                                int32_t* __restrict__ idx_out) {
+  constexpr int kThreads = THREADS;
+  constexpr int kWaves = Shape<THREADS>::kWaves, kItems = Shape<THREADS>::kItems, kChunk = Shape<THREADS>::kChunk;
+  static_assert(THREADS >= kBins, "one thread per digit in the histogram reduction");
   __shared__ uint32_t hist[kBins * kCopies];
   __shared__ uint32_t cnt[kBins];
-  __shared__ uint32_t wave_tot[kItems][kWaves];
+  __shared__ uint32_t wave_tot[4][kWaves];
 
   const int tid = threadIdx.x;
   const int lane = tid & (kWave - 1);
-  const int wave = tid / kWave;
+  const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);   // uniform: usable as a lane selector
   const float* row = scores + static_cast<int64_t>(blockIdx.x) * row_stride;
   int32_t* out = idx_out + static_cast<int64_t>(blockIdx.x) * k;
   const bool vec = ((reinterpret_cast<uintptr_t>(row) & 15u) == 0);
   constexpr bool resident = RESIDENT;
 
-  Span cur;
-  load_span(row, 0, T, vec, cur);
+  Span<kItems> cur;
+  load_span<THREADS>(row, 0, T, vec, cur);
   for (int i = tid; i < kBins * kCopies; i += kThreads) hist[i] = 0;
   __syncthreads();
 
@@ -115,9 +131,9 @@ __global__ __launch_bounds__(kThreads, RESIDENT ? 8 : 4) void select_topk_kernel
       histogram_span(cur, mask, prefix, shift, hist);
     } else {
       for (int64_t base = 0; base < T; base += kSpan) {
-        Span nxt;
+        Span<kItems> nxt;
         const int64_t nb = base + kSpan < T ? base + kSpan : 0;   // wrap: span 0 is needed again next
-        load_span(row, nb, T, vec, nxt);
+        load_span<THREADS>(row, nb, T, vec, nxt);
         histogram_span(cur, mask, prefix, shift, hist);
         cur = nxt;
       }
@@ -125,9 +141,9 @@ __global__ __launch_bounds__(kThreads, RESIDENT ? 8 : 4) void select_topk_kernel
     __syncthreads();
     if (tid < kBins) {
       uint32_t sum = 0;
-#pragma unroll
+#pragma unroll 8
       for (int c = 0; c < kCopies; ++c) {
-        const int slot = tid * kCopies + ((c + tid) & (kCopies - 1));
+        const int slot = (tid * kCopies + (tid & (kCopies - 1))) ^ c;   // copy (tid ^ c) mod 32: a different bank per lane
         sum += hist[slot];
         hist[slot] = 0;   // ready for the next pass
       }
@@ -167,56 +183,59 @@ __global__ __launch_bounds__(kThreads, RESIDENT ? 8 : 4) void select_topk_kernel
   const uint32_t tau = prefix;
   uint32_t gt_base = 0, eq_base = 0;
   for (int64_t base = 0; base < T; base += kSpan) {
-    Span nxt;
+    Span<kItems> nxt;
     if (!resident) {
       const int64_t nb = base + kSpan < T ? base + kSpan : 0;
-      load_span(row, nb, T, vec, nxt);
+      load_span<THREADS>(row, nb, T, vec, nxt);
     }
     // per item: (#greater, #equal) of this thread's 4 elements, packed 16 + 16 bits (a span holds
-    // at most 16384 elements), scanned across the block in element order
-    uint32_t mine[kItems], incl[kItems];
+    // at most 16384 elements), scanned across the block in element order, four items per round
 #pragma unroll
-    for (int c = 0; c < kItems; ++c) {
-      uint32_t g = 0, q = 0;
+    for (int c0 = 0; c0 < kItems; c0 += 4) {
+      if (c0 > 0) __syncthreads();   // wave_tot is rewritten
+      uint32_t excl[4];              // (greater, equal) of the earlier lanes of this wave, per item
 #pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        g += cur.key[c][e] > tau ? 1u : 0u;
-        q += cur.key[c][e] == tau ? 1u : 0u;
+      for (int j = 0; j < 4; ++j) {
+        uint32_t g = 0, q = 0;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          g += cur.key[c0 + j][e] > tau ? 1u : 0u;
+          q += cur.key[c0 + j][e] == tau ? 1u : 0u;
+        }
+        const uint32_t mine = g | (q << 16);
+        const uint32_t incl = wave_inclusive_scan(mine);
+        if (lane == kWave - 1) wave_tot[j][wave] = incl;
+        excl[j] = incl - mine;
       }
-      mine[c] = g | (q << 16);
-      incl[c] = wave_inclusive_scan(mine[c]);
-      if (lane == kWave - 1) wave_tot[c][wave] = incl[c];
-    }
-    __syncthreads();
-    uint32_t span_tot = 0;
+      __syncthreads();
+      // the 4 x kWaves wave totals are in element order: every wave scans them, one per lane
+      static_assert(4 * kWaves <= kWave, "one wave total per lane");
+      const uint32_t tot_mine = lane < 4 * kWaves ? (&wave_tot[0][0])[lane] : 0u;
+      const uint32_t tot_incl = wave_inclusive_scan(tot_mine);
+      const uint32_t tot_excl = tot_incl - tot_mine;
 #pragma unroll
-    for (int c = 0; c < kItems; ++c) {
-      uint32_t before = span_tot;            // all earlier items of the span
-      uint32_t item_tot = 0;
+      for (int j = 0; j < 4; ++j) {
+        // everything before this wave's part of the item, then this thread's place inside it
+        const uint32_t before =
+            static_cast<uint32_t>(__builtin_amdgcn_readlane(static_cast<int>(tot_excl), j * kWaves + wave)) + excl[j];
+        uint32_t gt_before = gt_base + (before & 0xffffu), eq_before = eq_base + (before >> 16);
+        const int32_t i0 = static_cast<int32_t>(base) + (c0 + j) * kChunk + tid * 4;   // T < 2^31
 #pragma unroll
-      for (int w = 0; w < kWaves; ++w) {
-        const uint32_t t = wave_tot[c][w];
-        if (w < wave) before += t;
-        item_tot += t;
-      }
-      span_tot += item_tot;
-      before += incl[c] - mine[c];
-      uint32_t gt_before = gt_base + (before & 0xffffu), eq_before = eq_base + (before >> 16);
-      const int64_t i0 = base + c * kChunk + static_cast<int64_t>(tid) * 4;
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        const uint32_t key = cur.key[c][e];
-        if (key > tau) {
-          out[gt_before + min(eq_before, krem)] = static_cast<int32_t>(i0 + e);
-          ++gt_before;
-        } else if (key == tau) {
-          if (eq_before < krem) out[gt_before + eq_before] = static_cast<int32_t>(i0 + e);
-          ++eq_before;
+        for (int e = 0; e < 4; ++e) {
+          const uint32_t key = cur.key[c0 + j][e];
+          if (key > tau) {
+            out[gt_before + min(eq_before, krem)] = i0 + e;
+            ++gt_before;
+          } else if (key == tau) {
+            if (eq_before < krem) out[gt_before + eq_before] = i0 + e;
+            ++eq_before;
+          }
         }
       }
+      const uint32_t round_tot = static_cast<uint32_t>(__builtin_amdgcn_readlane(static_cast<int>(tot_incl), kWave - 1));
+      gt_base += round_tot & 0xffffu;
+      eq_base += round_tot >> 16;
     }
-    gt_base += span_tot & 0xffffu;
-    eq_base += span_tot >> 16;
     if (!resident) {
       cur = nxt;
       __syncthreads();   // wave_tot is rewritten by the next span
@@ -229,10 +248,16 @@ __global__ __launch_bounds__(kThreads, RESIDENT ? 8 : 4) void select_topk_kernel
 void select_topk_launch(const float* scores, int64_t n_rows, int64_t T, int64_t row_stride, int64_t k,
                         int32_t* idx_out, hipStream_t st) {
   const dim3 grid(static_cast<unsigned>(n_rows));
-  if (T <= kSpan)
-    select_topk_kernel<true><<<grid, kThreads, 0, st>>>(scores, T, row_stride, k, idx_out);
+  if (T > kSpan) {
+    select_topk_kernel<1024, false><<<grid, 1024, 0, st>>>(scores, T, row_stride, k, idx_out);
+    return;
+  }
+  // A CU holds two 1024-thread blocks or four 512-thread ones.  Up to 512 rows every row gets a slot either way
+  // and the wider block finishes a row sooner; beyond that the narrower shape keeps twice the rows in flight.
+  if (n_rows <= 2 * 256)
+    select_topk_kernel<1024, true><<<grid, 1024, 0, st>>>(scores, T, row_stride, k, idx_out);
   else
-    select_topk_kernel<false><<<grid, kThreads, 0, st>>>(scores, T, row_stride, k, idx_out);
+    select_topk_kernel<512, true><<<grid, 512, 0, st>>>(scores, T, row_stride, k, idx_out);
 }
 
 }  // namespace kvp

@@ -59,6 +59,20 @@ def test_topk_strided_rows_unaligned():
     assert np.array_equal(got.cpu().numpy(), want)
 
 
+@pytest.mark.parametrize("T", [9, 3000, 8195, 16384])
+def test_topk_many_rows(T):
+    """More rows than the chip holds wide blocks for: the narrower block shape (8 items per thread)."""
+    _say("topk many rows", T)
+    rows = 530
+    s = workloads.make_scores(rows, T, seed=T).numpy()
+    s[1::7] = np.round(s[1::7] * 8) / 8                                # rows with heavy ties
+    s[2::7, ::2] = 0.0
+    if T > 40:
+        s[::3, T - 32:] = np.inf
+    for k in sorted({1, T // 3, T - 1, T}):
+        _check_topk(s, k)
+
+
 def test_topk_long_rows_many_ties():
     _say("topk long")
     T = 131072
