@@ -225,16 +225,21 @@ def cpu_baseline(K, V, bt, nb, cfg):
             "seconds": round(dt, 2)}
 
 
-def _time_loop(torch, fn, iters, warm=1):
+def _time_loop(torch, fn, iters, warm=3, batches=3):
+    """Median over `batches` event-timed batches of `iters` calls, after `warm` untimed calls (the clocks of an
+    idle GPU take a few milliseconds of load to settle)."""
     for _ in range(warm):
         fn()
-    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    a.record()
-    for _ in range(iters):
-        fn()
-    b.record()
-    torch.cuda.synchronize()
-    return a.elapsed_time(b) / iters * 1e-3
+    times = []
+    for _ in range(batches):
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(iters):
+            fn()
+        b.record()
+        torch.cuda.synchronize()
+        times.append(a.elapsed_time(b) / iters * 1e-3)
+    return sorted(times)[len(times) // 2]
 
 
 def side_measurements(kvp, workloads, torch, dev, K8, V8):
@@ -325,7 +330,29 @@ def side_measurements(kvp, workloads, torch, dev, K8, V8):
                                 "quantize_frac_hbm": round(alg5 / t5q / 1e9 / HBM_PEAK_GBS, 4),
                                 "dequantize_frac_hbm": round(alg5 / t5d / 1e9 / HBM_PEAK_GBS, 4),
                                 "compress_decompress_input_GBs": round(K5.numel() * 2 / (t5q + t5d) / 1e9, 1)}
-    del K5, q5, p5
+    del q5, p5
+    # attention scores at this shape (M = G*W = 224 window rows: the regime where the K reads count), then the
+    # keep-set from those scores
+    Q5 = workloads.make_q(c5["L"], c5["W"], c5["G"] * c5["H"], c5["D"], seed=0, device=dev)
+    sc5 = torch.empty(c5["L"], c5["H"], c5["T"], dtype=torch.float32, device=dev)
+    ws5 = torch.empty(kvp.kvp_score_workspace_bytes(c5["L"], c5["H"], c5["G"] * c5["H"], c5["W"], c5["T"]) + 16,
+                      dtype=torch.uint8, device=dev)
+    t5s = _time_loop(torch, lambda: kvp.kvp_score_tokens(Q5, K5, sc5, ws=ws5), 5)
+    rows5 = c5["L"] * c5["H"]
+    k5 = kvp.kvp_keep_count(c5["keep_ratio"], c5["T"])
+    idx5 = torch.empty(rows5, k5, dtype=torch.int32, device=dev)
+    t5sel = _time_loop(torch, lambda: kvp.kvp_select_topk(sc5.view(rows5, c5["T"]), k5, idx5), 10)
+    M5 = c5["G"] * c5["W"]
+    flops5 = 2 * 2.0 * rows5 * M5 * c5["T"] * c5["D"]
+    ops["long_context_score_select"] = {
+        "workload": f"{c5['L']}x{c5['H']}x{c5['D']}x{c5['T']} K plane, G={c5['G']}, W={c5['W']} (M={M5}), keep {k5}",
+        "score_ms": round(t5s * 1e3, 3), "score_TFLOPs": round(flops5 / t5s / 1e12, 1),
+        "score_frac_mfma": round(flops5 / t5s / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
+        "score_K_read_GBs": round(2 * K5.numel() * 2 / t5s / 1e9, 1),
+        "score_K_read_frac_hbm": round(2 * K5.numel() * 2 / t5s / 1e9 / HBM_PEAK_GBS, 4),
+        "select_us": round(t5sel * 1e6, 1), "select_GBs_alg": round(rows5 * (c5["T"] + k5) * 4 / t5sel / 1e9, 1),
+        "note": "scores come from kvp_score_tokens (two passes over K: both counted in score_K_read)"}
+    del K5, Q5, sc5, ws5, idx5
     # --- key-only importance scores (knorm, keydiff) on the resident K plane ---
     sc8 = torch.empty(L, H, T, dtype=torch.float32, device=dev)
     wsk = torch.empty(kvp.kvp_score_keys_workspace_bytes(L, H, T, kvp.KVP_SCORE_KEYDIFF) + 16, dtype=torch.uint8, device=dev)

@@ -15,7 +15,7 @@
 // Tiling.  A block is 8 waves and owns one key chunk of one (layer, kv head).  The window queries
 // (at most 512 rows) are staged once per block in LDS (row pitch 272 B so that the 16-byte operand
 // reads of 8 lanes cover all 32 banks).  Every wave then works alone, without block barriers: it
-// owns a run of 32-key tiles, loads a tile straight from global memory into MFMA operand registers
+// owns every 8th 32-key tile of the chunk, loads a tile straight from global memory into MFMA operand registers
 // (the next tile is fetched while the current one is consumed), and walks all query tiles against
 // it in a software pipeline (the MFMAs of query tile n+1 are issued before the vector-ALU work of
 // tile n).  The MFMA operand layout is the same for A and B (lane = row or column index mod 32,
@@ -88,6 +88,7 @@ __global__ __launch_bounds__((PASS_B ? kWavesB : kWavesA) * kWave, 2) void score
   constexpr int kThreads = kWavesPerBlock * kWave;
   __shared__ __attribute__((aligned(16))) uint16_t q_s[NQT * 32 * kPitch];
   __shared__ __attribute__((aligned(16))) float bias_s[PASS_B ? NQT * 32 : 4];
+  __shared__ __attribute__((aligned(16))) int32_t wpos_s[NQT * 32];   // window offset r mod W of query row r (masked tiles)
 
   const int lane = threadIdx.x & 63;
   const int wave = threadIdx.x >> 6;
@@ -108,9 +109,10 @@ __global__ __launch_bounds__((PASS_B ? kWavesB : kWavesA) * kWave, 2) void score
     }
     *reinterpret_cast<uint4*>(q_s + r * kPitch + part * 8) = v;
   }
-  if constexpr (PASS_B) {
+  for (int r = threadIdx.x; r < NQT * 32; r += kThreads) {
+    wpos_s[r] = r % a.W;
     // rows beyond M carry +inf: they contribute 2^-inf = 0
-    for (int r = threadIdx.x; r < NQT * 32; r += kThreads) bias_s[r] = a.bias[static_cast<int64_t>(lh) * a.Mrows + r];
+    if constexpr (PASS_B) bias_s[r] = a.bias[static_cast<int64_t>(lh) * a.Mrows + r];
   }
   __syncthreads();
 
@@ -147,7 +149,7 @@ __global__ __launch_bounds__((PASS_B ? kWavesB : kWavesA) * kWave, 2) void score
     if constexpr (!PASS_B) {
       // c[v] = raw dot product of key tk0 + acc_row(v) with query row qt*32 + lane%32
       if constexpr (MASKED) {
-        const int qpos = win0 + ((qt * 32 + (lane & 31)) % a.W);
+        const int qpos = win0 + wpos_s[qt * 32 + (lane & 31)];
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
           const int t = tk0 + acc_row(lane, v);
@@ -176,9 +178,12 @@ __global__ __launch_bounds__((PASS_B ? kWavesB : kWavesA) * kWave, 2) void score
         const int t = tk0 + (lane & 31);
         if (a.causal) {
 #pragma unroll
-          for (int v = 0; v < 16; ++v) {
-            const int r = qt * 32 + acc_row(lane, v);
-            if (t > win0 + (r % a.W)) c[v] = -INFINITY;
+          for (int g = 0; g < 4; ++g) {   // rows acc_row(lane, 4 g .. 4 g + 3), as for the bias
+            const int4 w4 = *reinterpret_cast<const int4*>(wpos_s + qt * 32 + g * 8 + (lane >> 5) * 4);
+            if (t > win0 + w4.x) c[4 * g + 0] = -INFINITY;
+            if (t > win0 + w4.y) c[4 * g + 1] = -INFINITY;
+            if (t > win0 + w4.z) c[4 * g + 2] = -INFINITY;
+            if (t > win0 + w4.w) c[4 * g + 3] = -INFINITY;
           }
         }
       }
@@ -256,16 +261,17 @@ __global__ __launch_bounds__((PASS_B ? kWavesB : kWavesA) * kWave, 2) void score
     }
   };
 
-  // ---- this wave's run of key tiles ----
-  const int keys_per_wave = a.chunk_keys / kWavesPerBlock;   // a multiple of 32
-  const int t_begin = chunk * a.chunk_keys + wave * keys_per_wave;
-  const int t_end = min(a.T, t_begin + keys_per_wave);
+  // ---- this wave's key tiles: every kWavesPerBlock-th tile of the chunk, so that the few masked tiles at the
+  //      end of a row (each costs more) are spread over the waves instead of all landing on the last one ----
+  constexpr int kTileStride = 32 * kWavesPerBlock;
+  const int t_begin = chunk * a.chunk_keys + wave * 32;
+  const int t_end = min(a.T, (chunk + 1) * a.chunk_keys);   // chunk_keys is a multiple of kTileStride
   if (t_begin < t_end) {
     uint4 kop[8], knext[8];
     load_key_tile(a, kbase, t_begin, lane, kop);
-    for (int tk0 = t_begin; tk0 < t_end; tk0 += 32) {
-      const bool more = tk0 + 32 < t_end;
-      if (more) load_key_tile(a, kbase, tk0 + 32, lane, knext);
+    for (int tk0 = t_begin; tk0 < t_end; tk0 += kTileStride) {
+      const bool more = tk0 + kTileStride < t_end;
+      if (more) load_key_tile(a, kbase, tk0 + kTileStride, lane, knext);
       const bool need_mask = (a.causal && tk0 + 32 > win0 + 1) || (tk0 + 32 > a.T);
       if (need_mask)
         key_tile(std::true_type{}, kop, tk0);

@@ -205,6 +205,26 @@ def test_long_context_select_full_rows():
     assert np.all(kept_min >= dropped_max)
 
 
+def test_long_context_score_full_shape_one_head():
+    """Attention scores at the long-context shape (28 x 4 heads x 131072 keys, M = 7 x 32 = 224 window rows,
+    outlier channels x 16): one (layer, head) pair against the oracle, every softmax row accounted for."""
+    kvp = _kvp()
+    c = workloads.CONFIGS["long_context_int2"]
+    L, T, H, D, G, W = c["L"], c["T"], c["H"], c["D"], c["G"], c["W"]
+    _say("long-context scores", (L, T, H, D), G, W)
+    K, _ = workloads.make_kv(L, T, H, D, seed=0, outlier_scale=c["outlier_scale"], device=DEV)
+    Q = workloads.make_q(L, W, G * H, D, seed=0, device=DEV)
+    s = kvp.kvp_score_tokens(Q, K, force_window=False)
+    torch.cuda.synchronize()
+    # each of the G*W softmax rows of every (layer, head) sums to one
+    assert torch.allclose(s.sum(-1), torch.full((L, H), float(G * W), device=DEV), rtol=1e-3)
+    l, h = 11, 2
+    ref = oracle.score_tokens(torch_bits(Q[l:l + 1, :, h * G:(h + 1) * G]), torch_bits(K[l:l + 1, :, h:h + 1]),
+                              force_window=False)[0, 0]
+    got = s[l, h].cpu().numpy()
+    assert np.all(np.abs(got - ref) <= 1e-2 * np.abs(ref) + 1e-4 * G * W / T)
+
+
 @pytest.mark.parametrize("pv_matrix_cores", [False, True], ids=["pv_vector_alu", "pv_matrix_cores"])
 def test_utility_sweep_context_properties_and_sampled_head(pv_matrix_cores):
     kvp = _kvp()
