@@ -30,10 +30,12 @@
 //     address check.  oracle_smooth_scores: library pooling, closed forms, brute force.
 //   oracle_score_keys (knorm, keydiff): pinned by closed forms (3-4-5 norms, identical / orthogonal /
 //     antipodal keys), scale invariance and a library float64 normalize + matmul.
-//   oracle_score_tokens / oracle_eval_configs: pinned by closed forms,
-//     invariants, a library float64 softmax on tiny shapes and an independent
-//     tiny brute force; the absolute values on random data are otherwise
-//     "parity unpinned" (no published value exists for them).
+//   oracle_score_tokens / oracle_eval_configs: pinned by closed forms (zero
+//     queries, one dominant key), the row-sum invariant, a library float64
+//     softmax / einsum recomputation on random inputs of small shape and a
+//     brute force written from the formulas (tests/test_oracle_select_score.py,
+//     tests/test_oracle_eval.py).  The paper prints no numeric value of either
+//     quantity, so there is no golden figure of its own to compare with.
 //
 // Precision: binary32 exactly where results are graded bit-exactly (scales,
 // codes, dequantized bf16), double where results are graded to a tolerance
