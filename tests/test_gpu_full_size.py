@@ -186,7 +186,7 @@ def test_per_channel_full_plane_sampled_groups(bits, group, asym):
         assert np.array_equal(got, od)
 
 
-def test_drop_then_quantize_70b_shape_sampled():
+def test_drop_then_quantize_70b_shape():
     kvp = _kvp()
     c = workloads.CONFIGS["llama3_70b_drop_int4"]
     L, T, H, D, G, W = 16, c["T"], c["H"], c["D"], c["G"], c["W"]          # 16 of the 80 layers (same grid shape per layer)
@@ -213,33 +213,32 @@ def test_drop_then_quantize_70b_shape_sampled():
     assert np.array_equal(idx_np, oracle.select_topk(s_np, k))           # every row
     assert idx_np.shape == (L * H, k) and np.all(np.diff(idx_np, axis=1) > 0)
     assert np.all(idx_np[:, -W:] == np.arange(T - W, T))
-    # gathered quantization: sampled slots hold the quantized source token
-    rng = np.random.default_rng(2)
-    n = 2048
-    ls, ss, hs = rng.integers(0, L, n), rng.integers(0, k, n), rng.integers(0, H, n)
-    tok = idx_np.reshape(L, H, k)[ls, hs, ss]
-    li, ti, hi, si = (torch.from_numpy(np.asarray(x)).to(DEV) for x in (ls, tok, hs, ss))
-    rows = torch_bits(K[li, ti.long(), hi])
-    oc, os_ = oracle.quantize(rows.reshape(1, -1, 1, D), c["bits"], c["group"])
-    assert np.array_equal(qk.codes[li, si, hi].cpu().numpy(), oc[0, :, 0])
-    assert np.array_equal(qk.scales[li, si, hi].cpu().numpy().view(np.uint32), os_[0, :, 0].view(np.uint32))
-    assert not bool(qk.codes[:, k:].any()) and not bool(qk.scales[:, k:].any())   # padding slots
-    # restore at the original positions: sampled kept rows equal the oracle's dequantization of their slot,
-    # rows of dropped tokens keep the previous pool contents
+    # gathered quantization and the restore at the original positions, every element, layer by layer:
+    # slot i of head h holds the quantized token keep_idx[l][h][i], padding slots are zero; restored rows of
+    # kept tokens equal the oracle's, rows of dropped tokens keep the previous pool contents (7.0)
+    from concurrent.futures import ThreadPoolExecutor
     bt, nb = workloads.make_block_table(T, 16, seed=0, device=DEV)
     pool = torch.full((L, nb, 16, H, D), 7.0, dtype=torch.bfloat16, device=DEV)
     pg = kvp.PagedKV(pool, bt, T)
     kvp.kvp_dequantize_paged_scatter(qk, idx.view(L, H, k), pg)
     torch.cuda.synchronize()
-    ident = np.arange((n + 15) // 16, dtype=np.int32)
-    od = oracle.dequantize_paged(oc, os_, c["bits"], c["group"], n, ident, len(ident), 16).reshape(-1, D)[:n]
-    blocks = bt.long()[ti.long() // 16]
-    assert np.array_equal(torch_bits(pool[li, blocks, ti.long() % 16, hi]), od)
-    kept = torch.zeros(L, H, T, dtype=torch.bool, device=DEV)
-    kept.scatter_(2, idx.view(L, H, k).long(), True)
-    tok_pool = pool[:, bt.long()].reshape(L, -1, H, D)[:, :T]                  # [L][T][H][D] in token order
-    dropped = ~kept.permute(0, 2, 1)                                           # [L][T][H]
-    assert bool((tok_pool[dropped] == 7.0).all())
+    btn = bt.cpu().numpy()
+    keep_np = idx_np.reshape(L, H, k)
+    seven = int(torch_bits(torch.tensor([7.0], dtype=torch.bfloat16))[0])
+
+    def check_layer(l):
+        oc, os_ = oracle.quantize(torch_bits(K[l:l + 1]), c["bits"], c["group"], keep_idx=keep_np[l:l + 1], Tp=qk.Tp)
+        ok = np.array_equal(qk.codes[l:l + 1].cpu().numpy(), oc)
+        ok &= np.array_equal(qk.scales[l:l + 1].cpu().numpy().view(np.uint32), os_.view(np.uint32))
+        ref_pool = np.full((1, nb, 16, H, D), seven, dtype=np.uint16)
+        oracle.dequantize_paged_scatter(oc, os_, None, c["bits"], c["group"], keep_np[l:l + 1], T, btn, nb, 16, pool=ref_pool)
+        ok &= np.array_equal(torch_bits(pool[l:l + 1]), ref_pool)
+        return bool(ok)
+
+    with ThreadPoolExecutor(max_workers=8) as ex:
+        results = list(ex.map(check_layer, range(L)))
+    assert all(results), [l for l, r in enumerate(results) if not r]
+    assert not bool(qk.codes[:, k:].any()) and not bool(qk.scales[:, k:].any())   # padding slots
 
 
 def test_long_context_select_full_rows():
