@@ -11,14 +11,15 @@
 //      nested (the ranking is a total order), so the tokens split into shells: shell j holds the
 //      tokens that enter the keep-set at the j-th smallest keep_k.  One kernel turns the lists into
 //      a permutation of the tokens ordered by shell;
-//   3. reference pass over all tokens in that order: O_full and sum O_full^2;
-//   4. ONE stream per distinct (bits, group): attention of the window rows over the tokens in shell
+//   3. ONE stream per distinct (bits, group): attention of the window rows over the tokens in shell
 //      order with K and V quantized and dequantized on the fly; at every shell boundary the running
-//      output is the output of that keep level and is compared with O_full.  Every candidate keep
-//      level of a codec therefore costs one pass over its largest keep-set instead of one pass each;
+//      output is the output of that keep level and is stored.  Every candidate keep level of a codec
+//      therefore costs one pass over its largest keep-set instead of one pass each.  The 16-bit
+//      stream also walks the tokens no level keeps: its last state is O_full (the reference);
+//   4. sum (O_level - O_full)^2 per stored output and sum O_full^2 (compare kernel);
 //   5. a reduction in a fixed order (deterministic) to loss[] and partial[].
 //
-// The attention kernel (steps 3 and 4) walks the tokens in tiles of 32.  Per tile: 256 threads
+// The attention kernel (step 3) walks the tokens in tiles of 32.  Per tile: 256 threads
 // load 32 K rows and 32 V rows (16 lanes per row, 8 channels per lane), run the bit-exact group
 // quantizer and dequantizer of quant_device.h on them, and stage K-hat and V-hat as bf16
 // in LDS.  Each of the 4 waves owns 32 of the block's 128 query rows (stationary MFMA operand in
@@ -222,6 +223,28 @@ __device__ __forceinline__ void stage_v_transposed(uint16_t* vt_s, uint4 vp, int
   *reinterpret_cast<uint2*>(vt_s + vt_row(part * 8 + 2 * j + 1) * kVtPitch + col) = odd;
 }
 
+// Work item of a block.  The streams of one (layer, kv head, row block) read the same K and V tiles, in the same
+// order and at about the same pace.  Workgroups go to the 8 XCDs (each with its own L2) round-robin by linear
+// id, so block b serves item (b mod 8) * ceil(items / 8) + b / 8: every XCD gets a contiguous run of items, with
+// the stream index varying fastest, and the streams of a cell find each other's tiles in their XCD's L2.
+struct WorkItem {
+  int rb, lh, stream;
+  bool valid;
+};
+constexpr int kXcds = 8;
+__device__ __forceinline__ WorkItem work_item(const EvalArgs& a) {
+  const int items = a.RB * a.L * a.Hkv * a.n_streams;
+  const int per_xcd = (items + kXcds - 1) / kXcds;
+  const int w = static_cast<int>(blockIdx.x % kXcds) * per_xcd + static_cast<int>(blockIdx.x / kXcds);
+  WorkItem it;
+  it.valid = static_cast<int>(blockIdx.x / kXcds) < per_xcd && w < items;
+  it.stream = w % a.n_streams;
+  const int cell = w / a.n_streams;
+  it.rb = cell % a.RB;
+  it.lh = cell / a.RB;
+  return it;
+}
+
 // One launch covers every stream; the 16-bit stream also walks the tokens no keep level holds and so ends
 // as the reference O_full.  Outputs are compared afterwards (compare_kernel).
 // PV_MFMA: the P.V product on the matrix cores (two-term bf16 split of P) instead of the vector ALU.
@@ -239,10 +262,12 @@ __global__ __launch_bounds__(kThreads, KVP_EVAL_WAVES_PER_SIMD) void attention_k
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int half = lane >> 5;
-  const int rb = blockIdx.x, lh = blockIdx.y;
+  const WorkItem item = work_item(a);
+  if (!item.valid) return;
+  const int rb = item.rb, lh = item.lh, stream = item.stream;
   const int l = lh / a.Hkv, h = lh - l * a.Hkv;
-  const int bits = a.streams[blockIdx.z].bits, group = a.streams[blockIdx.z].group;
-  const bool is_ref = static_cast<int>(blockIdx.z) == a.ref_stream;
+  const int bits = a.streams[stream].bits, group = a.streams[stream].group;
+  const bool is_ref = stream == a.ref_stream;
   const int32_t* order = a.order + static_cast<int64_t>(lh) * a.T;
   const uint16_t* kbase = a.k + static_cast<int64_t>(l) * a.k_sl + static_cast<int64_t>(h) * a.k_sh;
   const uint16_t* vbase = a.v + static_cast<int64_t>(l) * a.v_sl + static_cast<int64_t>(h) * a.v_sh;
@@ -274,7 +299,7 @@ __global__ __launch_bounds__(kThreads, KVP_EVAL_WAVES_PER_SIMD) void attention_k
   for (int i = 0; i < 64; ++i) o[i] = 0.0f;
   const int ty = tid >> 4, tx = tid & 15;
   // this block's output slots; each thread's 64 values of a level are contiguous
-  float* levels_out = a.o_levels + (((static_cast<int64_t>(lh) * a.RB + rb) * a.n_streams + blockIdx.z) * (a.n_levels + 1)) *
+  float* levels_out = a.o_levels + (((static_cast<int64_t>(lh) * a.RB + rb) * a.n_streams + stream) * (a.n_levels + 1)) *
                                        (kRowsPerBlock * kHeadDim) + tid * 64;
 
   // segments end at the keep levels (tiles never straddle a level boundary, so the state at a
@@ -484,43 +509,49 @@ __global__ __launch_bounds__(kThreads, KVP_EVAL_WAVES_PER_SIMD) void attention_k
 }
 
 // Squared distances between every stored level of every stream and the reference, and the reference's own
-// squared norm: block (row block, layer x head, stream), thread layout as in attention_kernel.
+// squared norm; one block per (row block, layer x head, stream).  A stored output is 256 runs of 64 floats (one
+// run per thread of attention_kernel); here consecutive threads read consecutive 16-byte pieces, and the
+// query row a piece belongs to follows from its position.
 template <bool PV_MFMA>
 __global__ __launch_bounds__(kThreads) void compare_kernel(const EvalArgs a) {
   __shared__ float red_s[4];
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int rb = blockIdx.x, lh = blockIdx.y, st = blockIdx.z;
+  const int tid = threadIdx.x;
+  const WorkItem item = work_item(a);
+  if (!item.valid) return;
+  const int rb = item.rb, lh = item.lh, st = item.stream;
   const int64_t cellrow = static_cast<int64_t>(lh) * a.RB + rb;
   const int64_t per_level = kRowsPerBlock * kHeadDim;
-  const float* ref = a.o_levels + ((cellrow * a.n_streams + a.ref_stream) * (a.n_levels + 1) + a.n_levels) * per_level + tid * 64;
-  // which of this thread's 64 values belong to live query rows
-  bool live[8];
-  const int ty = tid >> 4;
-#pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    const int rloc = PV_MFMA ? wave * 32 + (lane & 31) : ((i < 4) ? 4 * ty + i : 64 + 4 * ty + (i - 4));
-    live[i] = rb * kRowsPerBlock + rloc < a.M;
-  }
+  const float4* ref = reinterpret_cast<const float4*>(
+      a.o_levels + ((cellrow * a.n_streams + a.ref_stream) * (a.n_levels + 1) + a.n_levels) * per_level);
+  // piece f = 256 j + tid is piece (f mod 16) of the run of writer thread f / 16 = 16 j + tid / 16
+  const int q4 = tid & 15, i = q4 >> 1;   // accumulators 8 i .. 8 i + 7 of the writer
+  bool live[16];
   float4 r[16];
 #pragma unroll
-  for (int q4 = 0; q4 < 16; ++q4) r[q4] = reinterpret_cast<const float4*>(ref)[q4];
+  for (int j = 0; j < 16; ++j) {
+    const int writer = 16 * j + (tid >> 4);
+    const int ty = writer >> 4;
+    const int rloc = PV_MFMA ? (writer >> 6) * 32 + (writer & 31) : ((i < 4) ? 4 * ty + i : 64 + 4 * ty + (i - 4));
+    live[j] = rb * kRowsPerBlock + rloc < a.M;
+    r[j] = ref[256 * j + tid];
+  }
   if (st == a.ref_stream) {
     float sq = 0.0f;
 #pragma unroll
-    for (int q4 = 0; q4 < 16; ++q4)
-      if (live[q4 >> 1]) sq += r[q4].x * r[q4].x + r[q4].y * r[q4].y + r[q4].z * r[q4].z + r[q4].w * r[q4].w;
+    for (int j = 0; j < 16; ++j)
+      if (live[j]) sq += r[j].x * r[j].x + r[j].y * r[j].y + r[j].z * r[j].z + r[j].w * r[j].w;
     const float total = block_sum(sq, red_s);
     if (tid == 0) a.den_part[cellrow] = total;
   }
   for (int lev = 0; lev < a.n_levels; ++lev) {
-    const float4* val = reinterpret_cast<const float4*>(a.o_levels + ((cellrow * a.n_streams + st) * (a.n_levels + 1) + lev) * per_level +
-                                                        tid * 64);
+    const float4* val =
+        reinterpret_cast<const float4*>(a.o_levels + ((cellrow * a.n_streams + st) * (a.n_levels + 1) + lev) * per_level);
     float sq = 0.0f;
 #pragma unroll
-    for (int q4 = 0; q4 < 16; ++q4) {
-      const float4 v = val[q4];
-      const float dx = v.x - r[q4].x, dy = v.y - r[q4].y, dz = v.z - r[q4].z, dw = v.w - r[q4].w;
-      if (live[q4 >> 1]) sq += dx * dx + dy * dy + dz * dz + dw * dw;
+    for (int j = 0; j < 16; ++j) {
+      const float4 v = val[256 * j + tid];
+      const float dx = v.x - r[j].x, dy = v.y - r[j].y, dz = v.z - r[j].z, dw = v.w - r[j].w;
+      if (live[j]) sq += dx * dx + dy * dy + dz * dz + dw * dw;
     }
     const float total = block_sum(sq, red_s);
     if (tid == 0) a.num_part[(cellrow * a.n_streams + st) * a.n_levels + lev] = total;
@@ -709,7 +740,9 @@ extern "C" int32_t kvp_eval_configs_ex(const kvp_view* q_win, const kvp_view* k,
     }
   }
   build_order_kernel<<<dim3(static_cast<unsigned>(p.LH)), kOrderThreads, 0, st>>>(a);
-  const dim3 grid(static_cast<unsigned>(p.RB), static_cast<unsigned>(p.LH), static_cast<unsigned>(a.n_streams));
+  const int64_t items = static_cast<int64_t>(p.RB) * p.LH * a.n_streams;
+  if (items >= (1ll << 30)) return KVP_ERR_SHAPE;
+  const dim3 grid(static_cast<unsigned>(kXcds * ceil_div(items, kXcds)));
   if (flags & KVP_EVAL_PV_MATRIX_CORES) {
     attention_kernel<true><<<grid, kThreads, 0, st>>>(a);
     compare_kernel<true><<<grid, kThreads, 0, st>>>(a);
