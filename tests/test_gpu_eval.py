@@ -70,6 +70,18 @@ def test_many_rows_and_duplicates(pv_matrix_cores):
     assert loss[0] == loss[1]
 
 
+@BOTH_PV
+def test_no_16_bit_config_and_no_keep_all(pv_matrix_cores):
+    """No configuration asks for 16 bits and none keeps every token: the reference comes from a hidden stream that
+    walks the tokens no keep level holds as well."""
+    T = 150
+    cfgs = [(4, 64, 50), (8, 128, 100), (2, 32, 100)]
+    _case(2, 32, 4, 2, T, cfgs, seed=3, pv_matrix_cores=pv_matrix_cores)
+    _case(1, 16, 2, 1, 97, [(8, 32, 40)], seed=4, pv_matrix_cores=pv_matrix_cores)      # a single configuration
+    # the 16-bit codec is listed last and never with all tokens
+    _case(1, 32, 4, 1, T, [(2, 128, 75), (4, 32, 20), (16, 0, 75)], seed=5, pv_matrix_cores=pv_matrix_cores)
+
+
 def test_errors():
     kvp = _kvp()
     q = torch.zeros(1, 8, 4, 128, dtype=torch.bfloat16, device=DEV)
