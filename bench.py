@@ -307,6 +307,20 @@ def side_measurements(kvp, workloads, torch, dev, K8, V8):
         rot_d()
     t_graph_q = _time_loop(torch, gq.replay, 5) / n_rot
     t_graph_d = _time_loop(torch, gd.replay, 5) / n_rot
+    # scores and keep-set of the same single layer (M = G*W = 128 window rows, k = half the tokens)
+    Q1 = workloads.make_q(n_rot, c1["W"], c1["G"] * c1["H"], c1["D"], seed=0, device=dev)
+    qviews = [Q1[i:i + 1] for i in range(n_rot)]
+    sc1 = torch.empty(1, c1["H"], c1["T"], dtype=torch.float32, device=dev)
+    ws1 = torch.empty(kvp.kvp_score_workspace_bytes(1, c1["H"], c1["G"] * c1["H"], c1["W"], c1["T"]) + 16,
+                      dtype=torch.uint8, device=dev)
+    k1 = kvp.kvp_keep_count(c1["keep_ratio"], c1["T"])
+    idx1 = torch.empty(c1["H"], k1, dtype=torch.int32, device=dev)
+
+    def rot_s():
+        for i in range(n_rot):
+            kvp.kvp_score_tokens(qviews[i], views[i], sc1, ws=ws1)
+    t_rot_s = _time_loop(torch, rot_s, 3) / n_rot
+    t_sel1 = _time_loop(torch, lambda: kvp.kvp_select_topk(sc1.view(c1["H"], c1["T"]), k1, idx1), 50, warm=5)
     ops["single_layer_int8"] = {
         "workload": f"1x{c1['H']}x{c1['D']}x{c1['T']} plane (8 MiB), int8 g128; 'rotating' = {n_rot} independent copies in turn",
         "quantize_us_cache_resident": round(t_same_q * 1e6, 1), "dequantize_us_cache_resident": round(t_same_d * 1e6, 1),
@@ -314,8 +328,10 @@ def side_measurements(kvp, workloads, torch, dev, K8, V8):
         "quantize_GBs_alg_rotating": round(alg1 / t_rot_q / 1e9, 1), "dequantize_GBs_alg_rotating": round(alg1 / t_rot_d / 1e9, 1),
         "quantize_us_rotating_hip_graph": round(t_graph_q * 1e6, 1), "dequantize_us_rotating_hip_graph": round(t_graph_d * 1e6, 1),
         "quantize_GBs_alg_hip_graph": round(alg1 / t_graph_q / 1e9, 1), "dequantize_GBs_alg_hip_graph": round(alg1 / t_graph_d / 1e9, 1),
-        "note": "launch-bound: one call moves 16.3 MB (2 us at peak); times include the per-call launch path"}
-    del gq, gd, K1, q1, p1, views
+        "score_us_rotating": round(t_rot_s * 1e6, 1), "select_us": round(t_sel1 * 1e6, 1), "select_k": k1,
+        "note": "launch-bound: one quantize call moves 16.3 MB (2 us at peak); times include the per-call launch path; "
+                "a score call is three launches"}
+    del gq, gd, K1, q1, p1, views, Q1, qviews
     # --- long-context int2 config at its true shape (4 KV heads: 16 KiB pages, outlier channels x16) ---
     c5 = workloads.CONFIGS["long_context_int2"]
     K5, _ = workloads.make_kv(c5["L"], c5["T"], c5["H"], c5["D"], seed=0, outlier_scale=c5["outlier_scale"], device=dev)
