@@ -130,3 +130,30 @@ def test_gather_quantize_and_scatter_restore_random(seed):
     ref_pool = np.full((L, n_pages, 16, H, D), three, dtype=np.uint16)
     oracle.dequantize_paged_scatter(oc, os_, om, bits, group, keep, T, bt.cpu().numpy(), n_pages, 16, pool=ref_pool)
     assert np.array_equal(torch_bits(pool), ref_pool)
+
+
+@pytest.mark.parametrize("seed", range(5))
+@pytest.mark.parametrize("pv_matrix_cores", [False, True], ids=["pv_vector_alu", "pv_matrix_cores"])
+def test_eval_configs_random(seed, pv_matrix_cores):
+    kvp = _kvp()
+    rng, L, H, T, G, W = _shape(seed + 100)
+    T = min(max(T, 2), 600)                                   # the oracle is O(configs x rows x T x D)
+    L = min(L, 2)
+    W = max(1, min(W, T, 32))
+    n = int(rng.integers(1, 9))
+    cfgs = []
+    for _ in range(n):
+        bits = int(rng.choice([16, 8, 4, 2]))
+        group = 0 if bits == 16 else int(rng.choice([32, 64, 128]))
+        cfgs.append((bits, group, int(rng.choice([T, rng.integers(1, T + 1)]))))
+    # at most 8 distinct keep levels
+    levels = sorted({c[2] for c in cfgs})[:8]
+    cfgs = [c for c in cfgs if c[2] in levels]
+    print("[case] random eval", dict(seed=seed, L=L, H=H, T=T, G=G, W=W, cfgs=cfgs, pv_matrix_cores=pv_matrix_cores), flush=True)
+    K, V = workloads.make_kv(L, T, H, D, seed=seed)
+    Q = workloads.make_q(L, W, G * H, D, seed=seed)
+    loss = kvp.kvp_eval_configs(Q.to(DEV), K.to(DEV), V.to(DEV), cfgs, pv_matrix_cores=pv_matrix_cores)
+    torch.cuda.synchronize()
+    ref, _ = oracle.eval_configs(torch_bits(Q), torch_bits(K), torch_bits(V), cfgs)
+    loss = loss.cpu().numpy()
+    assert np.all(np.abs(loss - ref) <= 1e-2 * np.abs(ref) + 1e-5), (loss, ref)
