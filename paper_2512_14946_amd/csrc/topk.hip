@@ -15,7 +15,7 @@
 // when there are more rows than the chip holds wide blocks (the work is bound by vector-ALU
 // instruction issue, about 60 per key, so what counts then is rows in flight per CU).  Longer rows
 // are processed in 16384-element spans that are re-read (from L2 after the first pass) with the
-// next span's loads issued before the current span is consumed.  Every wave redoes the 256-bin
+// loads of the next two spans in flight while the current span is consumed.  Every wave redoes the 256-bin
 // digit search and the scan of the wave totals itself, so a pass costs two block barriers.
 
 #include "kvp_internal.h"
@@ -56,14 +56,26 @@ __device__ __forceinline__ void load_span(const float* row, int64_t base, int64_
 #pragma unroll
   for (int c = 0; c < Shape<THREADS>::kItems; ++c) {
     const int64_t i = base + c * Shape<THREADS>::kChunk + static_cast<int64_t>(threadIdx.x) * 4;
+    // raw bit patterns only: nothing here waits for the loads (slots beyond the row get a negative NaN, key 0)
     if (vec && i + 4 <= T) {
-      const float4 v = *reinterpret_cast<const float4*>(row + i);
-      s.key[c][0] = to_key(v.x); s.key[c][1] = to_key(v.y); s.key[c][2] = to_key(v.z); s.key[c][3] = to_key(v.w);
+      const uint4 v = *reinterpret_cast<const uint4*>(row + i);
+      s.key[c][0] = v.x; s.key[c][1] = v.y; s.key[c][2] = v.z; s.key[c][3] = v.w;
     } else {
 #pragma unroll
-      for (int e = 0; e < 4; ++e) s.key[c][e] = (i + e < T) ? to_key(row[i + e]) : 0u;
+      for (int e = 0; e < 4; ++e) s.key[c][e] = (i + e < T) ? __float_as_uint(row[i + e]) : 0xffffffffu;
     }
   }
+}
+
+// raw bit patterns -> keys, once the span is about to be consumed
+template <int ITEMS>
+__device__ __forceinline__ Span<ITEMS> to_keys(const Span<ITEMS>& raw) {
+  Span<ITEMS> s;
+#pragma unroll
+  for (int c = 0; c < ITEMS; ++c)
+#pragma unroll
+    for (int e = 0; e < 4; ++e) s.key[c][e] = to_key(__uint_as_float(raw.key[c][e]));
+  return s;
 }
 
 template <int ITEMS>
@@ -119,8 +131,19 @@ __global__ __launch_bounds__(THREADS, RESIDENT ? 8 : 4) void select_topk_kernel(
   const bool vec = ((reinterpret_cast<uintptr_t>(row) & 15u) == 0);
   constexpr bool resident = RESIDENT;
 
-  Span<kItems> cur;
-  load_span<THREADS>(row, 0, T, vec, cur);
+  // Streaming rows keep two spans in flight behind the one being consumed; the spans are visited cyclically
+  // (0 .. n-1, then 0 again for the next pass), so the prefetch stream never stops between passes.
+  const int64_t n_spans = (T + kSpan - 1) / kSpan;
+  int64_t fetch = 0;   // index of the next span to request
+  auto next_base = [&]() {
+    const int64_t b = fetch * kSpan;
+    fetch = fetch + 1 < n_spans ? fetch + 1 : 0;
+    return b;
+  };
+  Span<kItems> cur, ahead;   // cur holds keys, ahead (and far below) raw bits still in flight
+  load_span<THREADS>(row, next_base(), T, vec, cur);
+  if (!resident) load_span<THREADS>(row, next_base(), T, vec, ahead);
+  cur = to_keys(cur);
   for (int i = tid; i < kBins * kCopies; i += kThreads) hist[i] = 0;
   __syncthreads();
 
@@ -131,11 +154,11 @@ __global__ __launch_bounds__(THREADS, RESIDENT ? 8 : 4) void select_topk_kernel(
       histogram_span(cur, mask, prefix, shift, hist);
     } else {
       for (int64_t base = 0; base < T; base += kSpan) {
-        Span<kItems> nxt;
-        const int64_t nb = base + kSpan < T ? base + kSpan : 0;   // wrap: span 0 is needed again next
-        load_span<THREADS>(row, nb, T, vec, nxt);
+        Span<kItems> far;
+        load_span<THREADS>(row, next_base(), T, vec, far);
         histogram_span(cur, mask, prefix, shift, hist);
-        cur = nxt;
+        cur = to_keys(ahead);
+        ahead = far;
       }
     }
     __syncthreads();
@@ -183,11 +206,8 @@ __global__ __launch_bounds__(THREADS, RESIDENT ? 8 : 4) void select_topk_kernel(
   const uint32_t tau = prefix;
   uint32_t gt_base = 0, eq_base = 0;
   for (int64_t base = 0; base < T; base += kSpan) {
-    Span<kItems> nxt;
-    if (!resident) {
-      const int64_t nb = base + kSpan < T ? base + kSpan : 0;
-      load_span<THREADS>(row, nb, T, vec, nxt);
-    }
+    Span<kItems> far;
+    if (!resident) load_span<THREADS>(row, next_base(), T, vec, far);
     // per item: (#greater, #equal) of this thread's 4 elements, packed 16 + 16 bits (a span holds
     // at most 16384 elements), scanned across the block in element order, four items per round
 #pragma unroll
@@ -237,7 +257,8 @@ __global__ __launch_bounds__(THREADS, RESIDENT ? 8 : 4) void select_topk_kernel(
       eq_base += round_tot >> 16;
     }
     if (!resident) {
-      cur = nxt;
+      cur = to_keys(ahead);
+      ahead = far;
       __syncthreads();   // wave_tot is rewritten by the next span
     }
   }
