@@ -196,7 +196,10 @@ int32_t kvp_smooth_scores(const float* scores, int64_t n_rows, int64_t T, int64_
  *     loss[c] = sqrt( sum (O_c - O_full)^2 / sum O_full^2 )
  * sums over layers, query heads, window rows and channels.  cfgs is a HOST
  * array; loss is device fp32 [n_cfgs]; partial is NULL or device fp32
- * [L][n_cfgs][2] = (numerator, denominator) per layer. */
+ * [L][n_cfgs][2] = (numerator, denominator) per layer.  At most 64 configurations and 8 distinct
+ * keep_k values per call.  The workspace holds the scores, the keep lists and one fp32 output
+ * (64 KiB per 128 window rows) per (layer, kv head, distinct codec, keep level): about 1.5 GB for
+ * 40 configurations of a 32-layer, 8-kv-head context; ask kvp_eval_workspace_bytes. */
 int32_t kvp_eval_configs(const kvp_view* q_win, const kvp_view* k, const kvp_view* v, const kvp_config* cfgs,
                          int32_t n_cfgs, float* loss, float* partial, void* ws, size_t ws_bytes, void* stream);
 size_t kvp_eval_workspace_bytes(int64_t L, int64_t Hkv, int64_t Hq, int64_t W, int64_t T, int32_t n_cfgs);

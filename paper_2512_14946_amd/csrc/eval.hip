@@ -611,10 +611,11 @@ EvalPlan make_plan(int64_t L, int64_t Hkv, int64_t Hq, int64_t W, int64_t T, int
   p.idx = align256(static_cast<size_t>(levels) * p.LH * T * sizeof(int32_t));
   p.shell = align256(static_cast<size_t>(p.LH) * T);
   p.order = align256(static_cast<size_t>(p.LH) * T * sizeof(int32_t));
-  // every configuration may bring its own stream, plus the hidden 16-bit one
-  p.o_levels = align256(static_cast<size_t>(p.LH) * p.RB * (cfgs + 1) * (levels + 1) * kRowsPerBlock * kHeadDim * sizeof(float));
+  // distinct codecs: at most 3 bit widths x 3 group sizes, plus the 16-bit one (listed or hidden)
+  const int64_t streams = cfgs + 1 < 10 ? cfgs + 1 : 10;
+  p.o_levels = align256(static_cast<size_t>(p.LH) * p.RB * streams * (levels + 1) * kRowsPerBlock * kHeadDim * sizeof(float));
   p.den = align256(static_cast<size_t>(p.LH) * p.RB * sizeof(float));
-  p.num = align256(static_cast<size_t>(p.LH) * p.RB * (cfgs + 1) * levels * sizeof(float));
+  p.num = align256(static_cast<size_t>(p.LH) * p.RB * streams * levels * sizeof(float));
   p.layer = align256(static_cast<size_t>(L) * cfgs * 2 * sizeof(double));
   p.total = p.score_ws + p.scores + p.idx + p.shell + p.order + p.o_levels + p.den + p.num + p.layer;
   return p;
