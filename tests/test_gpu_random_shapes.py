@@ -36,29 +36,30 @@ def test_quantize_dequantize_random(seed):
     bits = int(rng.choice([8, 4, 2]))
     group = int(rng.choice([32, 64, 128]))
     asym, per_channel = bool(rng.integers(0, 2)), bool(rng.integers(0, 2))
+    bs = int(rng.choice([1, 4, 8, 16, 32]))                     # page size (a per-channel group holds whole pages)
     print("[case] random quantize", dict(seed=seed, L=L, H=H, T=T, bits=bits, group=group, asym=asym,
-                                         per_channel=per_channel), flush=True)
+                                         per_channel=per_channel, bs=bs), flush=True)
     K, _ = workloads.make_kv(L, T, H, D, seed=seed, outlier_scale=float(rng.choice([1.0, 8.0, 16.0])))
     Kd = K.to(DEV)
-    qp = kvp.alloc_qplane(L, T, H, D, bits, group, DEV, asymmetric=asym, per_channel=per_channel)
+    qp = kvp.alloc_qplane(L, T, H, D, bits, group, DEV, page=bs, asymmetric=asym, per_channel=per_channel)
     kvp.kvp_quantize(Kd, qp)
-    n_pages = (T + 15) // 16
+    n_pages = (T + bs - 1) // bs
     nb = n_pages + int(rng.integers(0, 5))                      # spare blocks stay untouched
     bt = torch.from_numpy(rng.permutation(nb)[:n_pages].astype(np.int32)).to(DEV)
-    pg = kvp.alloc_paged(L, T, H, D, bt, nb, 16, fill_nan=True)
+    pg = kvp.alloc_paged(L, T, H, D, bt, nb, bs, fill_nan=True)
     kvp.kvp_dequantize_paged(qp, pg)
     torch.cuda.synchronize()
     x, btn = torch_bits(K), bt.cpu().numpy()
     if per_channel:
         oc, os_, om = oracle.quantize_channel(x, bits, group, asym=asym, Tp=qp.Tp)
-        od = oracle.dequantize_paged_channel(oc, os_, om, bits, group, T, btn, nb, 16)
+        od = oracle.dequantize_paged_channel(oc, os_, om, bits, group, T, btn, nb, bs)
     elif asym:
         oc, os_, om = oracle.quantize_asym(x, bits, group, Tp=qp.Tp)
-        od = oracle.dequantize_paged_asym(oc, os_, om, bits, group, T, btn, nb, 16)
+        od = oracle.dequantize_paged_asym(oc, os_, om, bits, group, T, btn, nb, bs)
     else:
         oc, os_ = oracle.quantize(x, bits, group, Tp=qp.Tp)
         om = None
-        od = oracle.dequantize_paged(oc, os_, bits, group, T, btn, nb, 16)
+        od = oracle.dequantize_paged(oc, os_, bits, group, T, btn, nb, bs)
     assert np.array_equal(qp.codes.cpu().numpy(), oc)
     assert np.array_equal(qp.scales.cpu().numpy().view(np.uint32), os_.view(np.uint32))
     if om is not None:
@@ -111,11 +112,16 @@ def test_gather_quantize_and_scatter_restore_random(seed):
     K, _ = workloads.make_kv(L, T, H, D, seed=seed)
     keep = np.stack([np.stack([np.sort(rng.permutation(T)[:k]) for _ in range(H)]) for _ in range(L)]).astype(np.int32)
     keep_d = torch.from_numpy(keep).to(DEV)
-    qp = kvp.alloc_qplane(L, k, H, D, bits, group, DEV, asymmetric=asym)
-    kvp.kvp_quantize(K.to(DEV), qp, keep_idx=keep_d)
-    n_pages = (T + 15) // 16
+    bs = int(rng.choice([2, 8, 16, 64]))
+    n_pages = (T + bs - 1) // bs
     bt = torch.from_numpy(rng.permutation(n_pages).astype(np.int32)).to(DEV)
-    pool = torch.full((L, n_pages, 16, H, D), 3.0, dtype=torch.bfloat16, device=DEV)
+    # the source is the serving engine's paged pool (same block table), gathered through the keep lists
+    src_pool = torch.zeros(L, n_pages, bs, H, D, dtype=torch.bfloat16, device=DEV)
+    tok = torch.arange(T, device=DEV)
+    src_pool[:, bt.long()[tok // bs], tok % bs] = K.to(DEV)
+    qp = kvp.alloc_qplane(L, k, H, D, bits, group, DEV, page=bs, asymmetric=asym)
+    kvp.kvp_quantize(kvp.PagedKV(src_pool, bt, T), qp, keep_idx=keep_d)
+    pool = torch.full((L, n_pages, bs, H, D), 3.0, dtype=torch.bfloat16, device=DEV)
     kvp.kvp_dequantize_paged_scatter(qp, keep_d, kvp.PagedKV(pool, bt, T))
     torch.cuda.synchronize()
     x = torch_bits(K)
@@ -127,8 +133,8 @@ def test_gather_quantize_and_scatter_restore_random(seed):
     assert np.array_equal(qp.codes.cpu().numpy(), oc)
     assert np.array_equal(qp.scales.cpu().numpy().view(np.uint32), os_.view(np.uint32))
     three = int(torch_bits(torch.tensor([3.0], dtype=torch.bfloat16))[0])
-    ref_pool = np.full((L, n_pages, 16, H, D), three, dtype=np.uint16)
-    oracle.dequantize_paged_scatter(oc, os_, om, bits, group, keep, T, bt.cpu().numpy(), n_pages, 16, pool=ref_pool)
+    ref_pool = np.full((L, n_pages, bs, H, D), three, dtype=np.uint16)
+    oracle.dequantize_paged_scatter(oc, os_, om, bits, group, keep, T, bt.cpu().numpy(), n_pages, bs, pool=ref_pool)
     assert np.array_equal(torch_bits(pool), ref_pool)
 
 
