@@ -258,7 +258,6 @@ __global__ __launch_bounds__(kThreads, KVP_EVAL_WAVES_PER_SIMD) void attention_k
   __shared__ __attribute__((aligned(16))) float alpha_s[PV_MFMA ? 4 : kRowsPerBlock];
   __shared__ __attribute__((aligned(16))) float z_s[PV_MFMA ? 4 : kRowsPerBlock];
   __shared__ int tok_s[kTile];
-  __shared__ float red_s[4];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int half = lane >> 5;
@@ -581,7 +580,7 @@ __global__ __launch_bounds__(kFinishThreads) void finish_kernel(const EvalArgs a
     }
   }
   __syncthreads();
-  if (threadIdx.x < a.n_cfgs) {
+  if (static_cast<int>(threadIdx.x) < a.n_cfgs) {
     const int c = threadIdx.x;
     double num = 0.0, den = 0.0;
     for (int l = 0; l < a.L; ++l) {
