@@ -4,7 +4,6 @@ from __future__ import annotations
 import glob
 import os
 import subprocess
-import sys
 
 PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)

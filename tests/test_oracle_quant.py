@@ -12,7 +12,6 @@ from fractions import Fraction
 
 import numpy as np
 import pytest
-import torch
 
 import oracle
 import workloads
