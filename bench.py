@@ -35,7 +35,8 @@ def parse_args():
     ap.add_argument("--no-ops", action="store_true", help="skip the per-operation side measurements")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--only", default=None,
-                    help="profiling aid: run only one operation in a loop (quantize|dequantize|copy|score|select|eval)")
+                    help="profiling aid: run only one operation in a loop "
+                         "(quantize|dequantize|copy|score|select|select_many|select_long|eval)")
     return ap.parse_args()
 
 
@@ -491,6 +492,14 @@ def profile_only(args, kvp, workloads, torch, dev, K, V, qK, pK, bt, nb):
                 kvp.kvp_score_tokens(Qc, Kc, sc, ws=ws)
             else:
                 kvp.kvp_select_topk(sc.view(Ls * c["H"], c["T"]), k, idx)
+    elif args.only in ("select_many", "select_long"):
+        # 2560 rows x 16384 (more rows than block slots) or the long-context shape (112 rows x 131072)
+        rows, T = (2560, 16384) if args.only == "select_many" else (112, 131072)
+        s = workloads.make_scores(rows, T, seed=0, device=dev)
+        k = kvp.kvp_keep_count(0.3 if args.only == "select_many" else 0.1, T)
+        idx = torch.empty(rows, k, dtype=torch.int32, device=dev)
+        for _ in range(n):
+            kvp.kvp_select_topk(s, k, idx)
     elif args.only == "eval":
         c = workloads.CONFIGS["utility_sweep"]
         Ke, Ve = workloads.make_kv(c["L"], c["T"], c["H"], c["D"], seed=0, device=dev)
