@@ -36,7 +36,7 @@ def parse_args():
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--only", default=None,
                     help="profiling aid: run only one operation in a loop "
-                         "(quantize|dequantize|copy|score|select|select_many|select_long|eval)")
+                         "(quantize|dequantize|dequantize_identity|copy|score|select|select_many|select_long|eval)")
     return ap.parse_args()
 
 
@@ -468,8 +468,10 @@ def profile_only(args, kvp, workloads, torch, dev, K, V, qK, pK, bt, nb):
     if args.only == "quantize":
         for _ in range(n):
             kvp.kvp_quantize(K, qK)
-    elif args.only == "dequantize":
+    elif args.only in ("dequantize", "dequantize_identity"):
         kvp.kvp_quantize(K, qK)
+        if args.only == "dequantize_identity":   # pages in token order instead of the scattered table
+            pK = kvp.PagedKV(pK.pool, torch.arange(nb, dtype=torch.int32, device=dev), pK.T)
         for _ in range(n):
             kvp.kvp_dequantize_paged(qK, pK)
     elif args.only == "copy":

@@ -29,7 +29,8 @@ def _case(L, W, G, H, T, cfgs, seed, outlier=8.0, pv_matrix_cores=False):
     ref, ref_partial = oracle.eval_configs(torch_bits(Q), torch_bits(K), torch_bits(V), cfgs)
     assert np.all(np.abs(loss - ref) <= 1e-2 * np.abs(ref) + 1e-5), (loss, ref)
     assert np.allclose(partial[..., 1], ref_partial[..., 1], rtol=1e-3)
-    assert np.all(np.abs(partial[..., 0] - ref_partial[..., 0]) <= 3e-2 * ref_partial[..., 0] + 1e-7)
+    # the numerator is the square of the loss's numerator: twice the relative tolerance of the loss
+    assert np.all(np.abs(partial[..., 0] - ref_partial[..., 0]) <= 2e-2 * ref_partial[..., 0] + 1e-7)
     return loss, ref
 
 
