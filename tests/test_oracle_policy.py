@@ -84,3 +84,32 @@ def test_unbounded_first_tier_needs_no_operation_and_overfull_last_tier_is_an_er
         assert len(ops) == 1 and ops[0][3] == policy.INSERT
     with pytest.raises(ValueError):
         policy.insert(nbytes, quality, [1.0, 1.0], [(0.1 * GB, 20 * GB)], 1.0, [-1, -1], [0, 0], 0)
+
+
+def _golden_ops(kind):
+    return [tuple(int(x) for x in r) for r in _rows(kind)]
+
+
+def test_three_tier_cascade_and_tie_order_worked_by_hand():
+    # the instance and every candidate's utility drop are written out in the golden file
+    nbytes = [[4 * GB, 2 * GB], [4 * GB, 2 * GB], [4 * GB, 2 * GB], [2 * GB, 1 * GB]]
+    quality = [[1.0, 0.5], [1.0, 0.5], [1.0, 0.25], [1.0, 0.5]]
+    tiers = [(8 * GB, 8 * GB), (3 * GB, 4 * GB), (-1.0, 1 * GB)]
+    ctx_tier, ctx_cfg = [0, 0, -1, 1], [0, 0, 0, 0]
+    ops = policy.insert(nbytes, quality, [1.0] * 4, tiers, 1.0, ctx_tier, ctx_cfg, 2)
+    assert ops == _golden_ops("three_tiers")
+    assert ctx_tier == [1, 0, 0, 1] and ctx_cfg == [1, 0, 0, 1]
+    # the drops the derivation lists, from the utility function alone
+    u = policy.utility
+    assert u(1.0, 1.0, policy.ttft(4 * GB, 8 * GB), 1.0) - u(1.0, 0.5, policy.ttft(2 * GB, 8 * GB), 1.0) == 0.25
+    assert u(1.0, 0.5, policy.ttft(2 * GB, 8 * GB), 1.0) - u(1.0, 0.5, policy.ttft(2 * GB, 4 * GB), 1.0) == 0.25
+    assert u(1.0, 1.0, policy.ttft(2 * GB, 4 * GB), 1.0) - u(1.0, 1.0, policy.ttft(2 * GB, 1 * GB), 1.0) == 1.5
+
+
+def test_equal_drops_inside_one_context_compress_first_lowest_configuration():
+    nbytes, quality = [[4 * GB, 2 * GB, 2 * GB]], [[1.0, 0.25, 0.25]]
+    tiers = [(3 * GB, 8 * GB), (-1.0, 4 * GB)]
+    ctx_tier, ctx_cfg = [-1], [0]
+    ops = policy.insert(nbytes, quality, [1.0], tiers, 1.0, ctx_tier, ctx_cfg, 0)
+    assert ops == _golden_ops("one_context_tie")
+    assert ctx_tier == [0] and ctx_cfg == [1]

@@ -42,6 +42,26 @@ def test_two_context_figure(kvp):
     assert ttft == pytest.approx(0.5) and all(quality[j][ctx_cfg[j]] == 1.0 for j in range(2))
 
 
+def _golden_ops(kind):
+    path = os.path.join(os.path.dirname(__file__), "golden", "policy_examples.txt")
+    rows = [[p.strip() for p in line.split("|")] for line in open(path) if line.strip() and not line.startswith("#")]
+    return [tuple(int(x) for x in r[1:]) for r in rows if r[0] == kind]
+
+
+def test_hand_worked_three_tier_cascade_and_tie_order(kvp):
+    # instances and derivations: tests/golden/policy_examples.txt
+    nbytes = [[4 * GB, 2 * GB], [4 * GB, 2 * GB], [4 * GB, 2 * GB], [2 * GB, 1 * GB]]
+    quality = [[1.0, 0.5], [1.0, 0.5], [1.0, 0.25], [1.0, 0.5]]
+    tiers = [(8 * GB, 8 * GB), (3 * GB, 4 * GB), (-1.0, 1 * GB)]
+    ctx_tier, ctx_cfg = np.array([0, 0, -1, 1], np.int32), np.zeros(4, np.int32)
+    assert kvp.kvp_policy_insert(nbytes, quality, [1.0] * 4, tiers, 1.0, ctx_tier, ctx_cfg, 2) == _golden_ops("three_tiers")
+    assert ctx_tier.tolist() == [1, 0, 0, 1] and ctx_cfg.tolist() == [1, 0, 0, 1]
+    ctx_tier, ctx_cfg = np.array([-1], np.int32), np.zeros(1, np.int32)
+    got = kvp.kvp_policy_insert([[4 * GB, 2 * GB, 2 * GB]], [[1.0, 0.25, 0.25]], [1.0], [(3 * GB, 8 * GB), (-1.0, 4 * GB)],
+                                1.0, ctx_tier, ctx_cfg, 0)
+    assert got == _golden_ops("one_context_tie")
+
+
 @pytest.mark.parametrize("seed", range(20))
 def test_random_instances_match_oracle(kvp, seed):
     rng = np.random.default_rng(seed)
