@@ -149,6 +149,20 @@ int32_t kvp_score_tokens(const kvp_view* q_win, const kvp_view* k, int32_t causa
                          float* scores, void* ws, size_t ws_bytes, void* stream);
 size_t kvp_score_workspace_bytes(int64_t L, int64_t Hkv, int64_t Hq, int64_t W, int64_t T);
 
+/* kvp_score_tokens for callers that cannot allocate device memory or carry a workspace (code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): the same kernels and the
+ * same results, bit for bit, with the scratch in a fixed device array inside the library
+ * (KVP_SCORE_STATIC_SCRATCH_BYTES per GPU, held until the process ends).  The call allocates and
+ * frees nothing and calls no allocating routine.  Shapes whose kvp_score_workspace_bytes() exceeds
+ * the array return KVP_ERR_WORKSPACE and enqueue nothing (4 MiB covers one layer of every shape up
+ * to Hkv = 8, G*W = 512, T = 131072, and whole small contexts).  All calls on one GPU share the one
+ * array: calls that may overlap on that GPU (different streams, different host threads) race and
+ * must be ordered by the caller; calls on one stream are ordered by the stream.  The array keeps
+ * the previous call's contents; every word a call reads it has written itself first. */
+#define KVP_SCORE_STATIC_SCRATCH_BYTES (4u << 20)
+int32_t kvp_score_tokens_static(const kvp_view* q_win, const kvp_view* k, int32_t causal, int32_t force_window,
+                                float* scores, void* stream);
+
 /* Key-only token importance of the paper's two other token-dropping methods
  * (Evaluation, Baselines): knorm scores a token by the L2 norm of its key (low
  * norms are dropped); keydiff by the average cosine similarity of its key to

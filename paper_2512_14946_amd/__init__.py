@@ -8,6 +8,7 @@ from .kvp import (  # noqa: F401
     KVPError, PagedKV, QPlane, alloc_paged, alloc_qplane, kvp_copy_bytes, kvp_dequantize_paged,
     kvp_dequantize_paged_scatter,
     kvp_eval_configs, kvp_eval_workspace_bytes, kvp_keep_count, kvp_quantize, kvp_score_tokens,
+    kvp_score_tokens_static, KVP_SCORE_STATIC_SCRATCH_BYTES,
     KVP_EVAL_PV_MATRIX_CORES, KVP_OP_COMPRESS, KVP_OP_EVICT, KVP_OP_INSERT, kvp_policy_insert, kvp_utility_table,
     KVP_SCORE_KEYDIFF, KVP_SCORE_KNORM, kvp_score_keys, kvp_score_keys_workspace_bytes,
     kvp_score_workspace_bytes, kvp_select_topk, kvp_select_workspace_bytes, kvp_smooth_scores, kvp_strerror,

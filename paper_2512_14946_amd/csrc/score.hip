@@ -29,6 +29,7 @@
 // the common tile carries no mask arithmetic.  Every key is owned by exactly one wave: no atomics,
 // deterministic output.
 
+#include <mutex>
 #include <type_traits>
 
 #include "kvp_internal.h"
@@ -422,4 +423,58 @@ extern "C" size_t kvp_score_workspace_bytes(int64_t L, int64_t Hkv, int64_t Hq, 
 extern "C" int32_t kvp_score_tokens(const kvp_view* q_win, const kvp_view* k, int32_t causal, int32_t force_window,
                                     float* scores, void* ws, size_t ws_bytes, void* stream) {
   return kvp::score_tokens_impl(q_win, k, causal, force_window, scores, ws, ws_bytes, kvp::as_stream(stream));
+}
+
+// ---- kvp_score_tokens_static: the same kernels with their scratch in a device array of the library ----
+//
+// `scratch` is the host-side stand-in of the device array: host code never passes it to a kernel.  Its
+// device address is looked up once per device (every GPU holds its own copy at its own address) and
+// only that address is used from then on.
+namespace kvp {
+namespace {
+
+static __device__ __align__(256) unsigned char scratch[KVP_SCORE_STATIC_SCRATCH_BYTES];
+
+constexpr int kMaxDevices = 64;
+std::mutex scratch_mutex;
+void* scratch_ptr[kMaxDevices] = {};   // device address of `scratch` on device i, once looked up
+
+// Device address of the current device's copy of `scratch` (nullptr + rc on failure).  Allocates nothing.
+int32_t static_scratch(void** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return KVP_ERR_LAUNCH;
+  std::lock_guard<std::mutex> lock(scratch_mutex);
+  if (!scratch_ptr[dev]) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) {
+      (void)hipGetLastError();
+      return KVP_ERR_LAUNCH;
+    }
+    scratch_ptr[dev] = p;
+  }
+  *out = scratch_ptr[dev];
+  return KVP_OK;
+}
+
+}  // namespace
+}  // namespace kvp
+
+extern "C" int32_t kvp_score_tokens_static(const kvp_view* q_win, const kvp_view* k, int32_t causal,
+                                           int32_t force_window, float* scores, void* stream) {
+  using namespace kvp;
+  // size check first (host arithmetic only), so that an oversized request fails before any lookup
+  int32_t rc = check_view(q_win);
+  if (rc != KVP_OK) return rc;
+  rc = check_view(k);
+  if (rc != KVP_OK) return rc;
+  if (q_win->H % k->H != 0) return KVP_ERR_SHAPE;
+  if (kvp_score_workspace_bytes(k->L, k->H, q_win->H, q_win->T, k->T) > KVP_SCORE_STATIC_SCRATCH_BYTES)
+    return KVP_ERR_WORKSPACE;
+  void* ptr = nullptr;
+  rc = static_scratch(&ptr);
+  if (rc != KVP_OK) return rc;
+  // every word of the scratch that pass B and the combine step read is written earlier in the same call
+  // (pass A stores the statistics of all chunks and all padded rows), so nothing has to be cleared
+  return score_tokens_impl(q_win, k, causal, force_window, scores, ptr, KVP_SCORE_STATIC_SCRATCH_BYTES,
+                           as_stream(stream));
 }

@@ -70,6 +70,8 @@ def _load(path: str = _LIB_PATH):
     lib.kvp_dequantize_paged_scatter.argtypes = [P(_QPlane), _vp, P(_Paged), _vp]
     lib.kvp_score_tokens.restype = _i32
     lib.kvp_score_tokens.argtypes = [P(_View), P(_View), _i32, _i32, _vp, _vp, _sz, _vp]
+    lib.kvp_score_tokens_static.restype = _i32
+    lib.kvp_score_tokens_static.argtypes = [P(_View), P(_View), _i32, _i32, _vp, _vp]
     lib.kvp_score_workspace_bytes.restype = _sz
     lib.kvp_score_workspace_bytes.argtypes = [_i64] * 5
     lib.kvp_score_keys.restype = _i32
@@ -295,6 +297,23 @@ def kvp_score_tokens(q_win: torch.Tensor, k: torch.Tensor, scores: torch.Tensor 
     qv, kv = _view(q_win), _view(k)
     _check(_lib.kvp_score_tokens(ctypes.byref(qv), ctypes.byref(kv), int(causal), int(force_window),
                                  scores.data_ptr(), wp, wb, _stream(stream)), "kvp_score_tokens")
+    return scores
+
+
+KVP_SCORE_STATIC_SCRATCH_BYTES = 4 << 20
+
+
+def kvp_score_tokens_static(q_win: torch.Tensor, k: torch.Tensor, scores: torch.Tensor, causal: bool = True,
+                            force_window: bool = True, stream=None) -> torch.Tensor:
+    """kvp_score_tokens with the scratch in the library's own fixed device array: nothing is allocated,
+    here or in the library, so `scores` must be supplied (contiguous f32 [L][Hkv][T])."""
+    _need_cuda(q_win, k, scores)
+    L, T, Hkv, _ = k.shape
+    if scores.dtype != torch.float32 or not scores.is_contiguous() or tuple(scores.shape) != (L, Hkv, T):
+        raise ValueError("scores must be contiguous float32 [L][Hkv][T]")
+    qv, kv = _view(q_win), _view(k)
+    _check(_lib.kvp_score_tokens_static(ctypes.byref(qv), ctypes.byref(kv), int(causal), int(force_window),
+                                        scores.data_ptr(), _stream(stream)), "kvp_score_tokens_static")
     return scores
 
 

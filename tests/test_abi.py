@@ -89,6 +89,26 @@ def test_validation_rejects_before_any_launch(lib):
     assert lib.kvp_score_keys(None, 0, None, None, 0, None) == -1
 
 
+def test_static_scratch_entry_point_rejects_oversized_shapes_on_the_host(lib):
+    # the size check is host arithmetic on the structs and comes before any GPU call: fake, aligned, never
+    # dereferenced pointers are enough
+    class View(ctypes.Structure):
+        _fields_ = [("ptr", ctypes.c_void_p)] + [(n, ctypes.c_int64) for n in ("L", "T", "H", "D", "sl", "st", "sh")]
+    lib.kvp_score_tokens_static.restype = ctypes.c_int32
+    lib.kvp_score_tokens_static.argtypes = [ctypes.POINTER(View)] * 2 + [ctypes.c_int32] * 2 + [ctypes.c_void_p] * 2
+    lib.kvp_score_workspace_bytes.restype = ctypes.c_size_t
+    lib.kvp_score_workspace_bytes.argtypes = [ctypes.c_int64] * 5
+    L, T, H, G, W = 80, 16384, 8, 8, 64
+    assert lib.kvp_score_workspace_bytes(L, H, G * H, W, T) > (4 << 20)
+    k = View(4096, L, T, H, 128, T * H * 128, H * 128, 128)
+    q = View(8192, L, W, G * H, 128, W * G * H * 128, G * H * 128, 128)
+    assert lib.kvp_score_tokens_static(ctypes.byref(q), ctypes.byref(k), 1, 1, 4096, None) == -5
+    assert lib.kvp_score_tokens_static(None, None, 1, 1, None, None) == -1
+    # one layer of the same shape fits
+    assert lib.kvp_score_workspace_bytes(1, H, G * H, W, T) <= (4 << 20)
+    assert lib.kvp_score_workspace_bytes(1, 8, 64, 64, 131072) <= (4 << 20)
+
+
 def test_binding_refuses_cpu_tensors():
     import torch
     import paper_2512_14946_amd as kvp
