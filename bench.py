@@ -24,6 +24,7 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16
 VALU_FP32_PEAK_TFLOPS = 78.6    # 256 CU x 4 SIMD x 16 lanes x 2 flop x 2.4 GHz, no packed fp32
+VALU_FP32_PUBLISHED_TFLOPS = 157.3   # published fp32 vector peak (packed fp32)
 
 
 def parse_args():
@@ -50,13 +51,20 @@ def event_ms(pairs):
     return [a.elapsed_time(b) for a, b in pairs]
 
 
-def traffic_from_profiles(name: str):
-    """HBM bytes per launch measured offline with rocprofv3 --pmc, if the summary is committed."""
+def profile_figures(name: str):
+    """Figures recorded in a committed rocprofv3 summary: HBM bytes per launch (two --pmc runs, scaled by the copy
+    kernel's reading) and the kernel's average launch time under --kernel-trace."""
     path = os.path.join(ROOT, "profiles", name)
-    if not os.path.exists(path):
-        return None
-    m = re.search(r"traffic_bytes_per_launch:\s*([0-9.eE+]+)", open(path).read())
-    return float(m.group(1)) if m else None
+    out = {}
+    if os.path.exists(path):
+        text = open(path).read()
+        m = re.search(r"traffic_bytes_per_launch:\s*([0-9.eE+]+)", text)
+        if m:
+            out["traffic"] = float(m.group(1))
+        m = re.search(r"avg_launch_us:\s*([0-9.eE+]+)", text)
+        if m:
+            out["launch_ms"] = float(m.group(1)) * 1e-3
+    return out
 
 
 def main():
@@ -132,16 +140,36 @@ def main():
     q_ms = [m for e in marks for m in event_ms([(e[0], e[1]), (e[1], e[2])])]
     d_ms = [m for e in marks for m in event_ms([(e[2], e[3]), (e[3], e[4])])]
     q_avg, d_avg = sum(q_ms) / len(q_ms), sum(d_ms) / len(d_ms)
-    achieved = alg_bytes_per_launch / (q_avg * 1e-3) / 1e9
-    roofline = {
-        "bound": "hbm", "kernel": f"quantize_kernel<{bits},{group},linear>", "achieved": round(achieved, 1),
-        "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-        "traffic": traffic_from_profiles("quantize_int4g64_llama3_8b_pmc.md"),
-        "algorithmic_bytes_per_launch": alg_bytes_per_launch, "avg_launch_ms": round(q_avg, 4),
-        "dequantize": {"kernel": f"dequantize_paged_kernel<{bits},{group}>", "avg_launch_ms": round(d_avg, 4),
-                       "achieved": round(alg_bytes_per_launch / (d_avg * 1e-3) / 1e9, 1),
-                       "frac": round(alg_bytes_per_launch / (d_avg * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)},
-    }
+
+    def kernel_entry(name, avg_ms, profile):
+        """Roofline figures of one kernel of the step: algorithmic bytes over the launch time measured with events
+        inside the timed steps; HBM traffic and the profiler's own launch time come from the committed rocprofv3
+        summary of the same command (they are not re-measured by this run, and the entry says so)."""
+        got = alg_bytes_per_launch / (avg_ms * 1e-3) / 1e9
+        prof = profile_figures(profile)
+        e = {"kernel": name, "avg_launch_ms": round(avg_ms, 4), "achieved": round(got, 1),
+             "frac": round(got / HBM_PEAK_GBS, 4), "share_of_step": round(2 * avg_ms / ms_per_step, 3),
+             "traffic": prof.get("traffic"), "traffic_source": f"rocprofv3 --pmc, offline: profiles/{profile}",
+             "profile_avg_launch_ms": prof.get("launch_ms")}
+        if prof.get("launch_ms") and abs(avg_ms - prof["launch_ms"]) > 0.05 * prof["launch_ms"]:
+            e["warning"] = ("launch time differs by more than 5 % from the profiled one: the traffic figure may "
+                            "describe an older build of this kernel")
+        return e
+
+    sym = "symmetric"
+    q_entry = kernel_entry(f"quantize_kernel<{bits},{group},{sym},linear>", q_avg, "quantize_int4g64_llama3_8b_pmc.md")
+    d_entry = kernel_entry(f"dequantize_paged_kernel<{bits},{group},{sym},paged>", d_avg,
+                           "dequantize_paged_int4g64_llama3_8b_pmc.md")
+    # the kernel with the larger share of the step is the headline; the other one rides along
+    first, second = (d_entry, q_entry) if d_avg >= q_avg else (q_entry, d_entry)
+    roofline = {"bound": "hbm", "kernel": first["kernel"], "achieved": first["achieved"], "peak": HBM_PEAK_GBS,
+                "unit": "GB/s", "frac": first["frac"], "traffic": first["traffic"],
+                "traffic_source": first["traffic_source"], "algorithmic_bytes_per_launch": alg_bytes_per_launch,
+                "avg_launch_ms": first["avg_launch_ms"], "profile_avg_launch_ms": first["profile_avg_launch_ms"],
+                "share_of_step": first["share_of_step"], "secondary": second}
+    if "warning" in first:
+        roofline["warning"] = first["warning"]
+    achieved = first["achieved"]
 
     # plain copy of the same plane: the practical ceiling of a streaming kernel on this part
     tmp = torch.empty_like(K)
@@ -160,7 +188,7 @@ def main():
 
     cpu = None
     if not args.no_cpu:
-        cpu = cpu_baseline(K, V, bt, nb, cfg)
+        cpu = cpu_baseline(K, V, bt, nb, cfg, workloads)
 
     ops = None
     if not args.no_ops:
@@ -176,8 +204,8 @@ def main():
         "config": {"workload": "llama3_8b_int4_paged", "shape": f"{L}x{H}x{D}x{T} bf16 K and V",
                    "codec": f"int{bits} group {group}", "page_tokens": bs, "input_bytes": input_bytes,
                    "step": "quantize(K), quantize(V), dequantize_paged(K), dequantize_paged(V)"},
-        "pct_of_hbm_peak_per_op": {"quantize": round(100 * roofline["frac"], 1),
-                                   "dequantize": round(100 * roofline["dequantize"]["frac"], 1)},
+        "pct_of_hbm_peak_per_op": {"quantize": round(100 * q_entry["frac"], 1),
+                                   "dequantize": round(100 * d_entry["frac"], 1)},
         "roofline": roofline,
         "cpu_baseline": cpu,
         "ops": ops,
@@ -185,17 +213,19 @@ def main():
     print(json.dumps(out))
 
 
-def cpu_baseline(K, V, bt, nb, cfg):
-    """The CPU oracle, as it stands, on a bounded sample of the same workload (layers split over threads)."""
+def cpu_baseline(K, V, bt, nb, cfg, workloads):
+    """The CPU oracle, as it stands, on bounded samples of the same workloads: quantize + dequantize_paged of the
+    headline configuration on all host threads (`value`) and on one core, then measured slices of the score,
+    select and proxy oracles with their full-configuration times extrapolated linearly (and labelled so)."""
     import numpy as np
+    import torch
     import oracle
     oracle.build()
     sample_layers = min(32, K.shape[0])
     cores = min(os.cpu_count() or 1, 16)
     T, bs, bits, group = cfg["T"], cfg["bs"], cfg["bits"], cfg["group"]
-    kb = K[:sample_layers].cpu().view(__import__("torch").int16).numpy().view(np.uint16)
-    vb = V[:sample_layers].cpu().view(__import__("torch").int16).numpy().view(np.uint16)
-    btn = bt.cpu().numpy()
+    kb = K[:sample_layers].cpu().view(torch.int16).numpy().view(np.uint16)
+    vb = V[:sample_layers].cpu().view(torch.int16).numpy().view(np.uint16)
     # split every layer in token slabs so that all threads have work; each slab is a whole number of pages
     slabs = max(1, cores * 2 // sample_layers)
     slab_tokens = (T // slabs) // bs * bs
@@ -220,10 +250,57 @@ def cpu_baseline(K, V, bt, nb, cfg):
     with ThreadPoolExecutor(max_workers=cores) as ex:
         done = sum(ex.map(run, jobs))
     dt = time.perf_counter() - t0
+    # the same work on ONE core: two layers of K
+    t0 = time.perf_counter()
+    one = sum(run((kb, l, 0, T)) for l in range(min(2, sample_layers)))
+    dt1 = time.perf_counter() - t0
+
+    def bits_of(t):
+        return t.cpu().contiguous().view(torch.int16).numpy().view(np.uint16)
+
+    slices = {}
+    # scores: one (layer, kv head) of the 70B-shaped configuration (M = 512 rows x 16384 keys)
+    c = workloads.CONFIGS["llama3_70b_drop_int4"]
+    Ks, _ = workloads.make_kv(1, c["T"], 1, c["D"], seed=0)
+    Qs = workloads.make_q(1, c["W"], c["G"], c["D"], seed=0)
+    t0 = time.perf_counter()
+    sc = oracle.score_tokens(bits_of(Qs), bits_of(Ks))
+    ds = time.perf_counter() - t0
+    cells = c["L"] * c["H"]
+    slices["score_tokens"] = {"sample": f"1 of {cells} (layer, kv head) cells of llama3_70b_drop_int4, one core",
+                              "seconds": round(ds, 3), "full_config_seconds_one_core": round(ds * cells, 1),
+                              "extrapolated": True}
+    # select: 8 of the 640 score rows
+    rows = np.ascontiguousarray(np.tile(np.where(np.isfinite(sc[0]), sc[0], 0.0).astype(np.float32), (8, 1)))
+    k = oracle.keep_count(c["keep_ratio"], c["T"])
+    t0 = time.perf_counter()
+    oracle.select_topk(rows, k)
+    dsel = time.perf_counter() - t0
+    slices["select_topk"] = {"sample": f"8 of {cells} rows of {c['T']} scores, k = {k}, one core", "seconds": round(dsel, 4),
+                             "full_config_seconds_one_core": round(dsel * cells / 8, 2), "extrapolated": True}
+    # proxy: one (layer, kv head) cell of one context of the sweep, 4 of the 40 configurations
+    c = workloads.CONFIGS["utility_sweep"]
+    Ke, Ve = workloads.make_kv(1, c["T"], 1, c["D"], seed=0)
+    Qe = workloads.make_q(1, c["W"], c["G"], c["D"], seed=0)
+    sub = [(16, 0, c["T"]), (8, 128, c["T"]), (4, 64, c["T"] // 2), (2, 32, c["T"] // 4)]
+    t0 = time.perf_counter()
+    oracle.eval_configs(bits_of(Qe), bits_of(Ke), bits_of(Ve), sub)
+    de = time.perf_counter() - t0
+    n_cfg = (1 + len(c["bits_set"]) * len(c["group_set"])) * (len(c["keep_ratios"]) + 1)
+    cells = c["L"] * c["H"]
+    slices["eval_configs"] = {"sample": f"1 of {cells} cells of one context of utility_sweep, {len(sub)} of {n_cfg} "
+                                        "configurations, one core", "seconds": round(de, 3),
+                              "one_context_seconds_one_core": round(de * cells * n_cfg / len(sub), 1),
+                              "full_config_seconds_one_core": round(de * cells * n_cfg / len(sub) * c["n_ctx"], 0),
+                              "extrapolated": True, "note": "the oracle recomputes every configuration from scratch; "
+                              "its cost is taken as linear in cells, configurations and contexts"}
     return {"value": round(done / dt / 1e9, 3), "unit": "GB/s", "cores": cores, "kind": "oracle",
             "sample": f"{sample_layers} of {K.shape[0]} layers of the same K and V ({done / 2**20:.0f} MiB of input), "
                       f"quantize + dequantize_paged, {len(jobs)} token slabs over {cores} threads",
-            "seconds": round(dt, 2)}
+            "seconds": round(dt, 2),
+            "one_core": {"value": round(one / dt1 / 1e9, 3), "unit": "GB/s", "cores": 1,
+                         "sample": f"{min(2, sample_layers)} layers of K ({one / 2**20:.0f} MiB)", "seconds": round(dt1, 2)},
+            "slices": slices}
 
 
 def _time_loop(torch, fn, iters, warm=3, batches=3):
@@ -358,7 +435,8 @@ def side_measurements(kvp, workloads, torch, dev, K8, V8):
     rows5 = c5["L"] * c5["H"]
     k5 = kvp.kvp_keep_count(c5["keep_ratio"], c5["T"])
     idx5 = torch.empty(rows5, k5, dtype=torch.int32, device=dev)
-    t5sel = _time_loop(torch, lambda: kvp.kvp_select_topk(sc5.view(rows5, c5["T"]), k5, idx5), 10)
+    wsel5 = torch.empty(kvp.kvp_select_workspace_bytes(rows5, c5["T"], k5), dtype=torch.uint8, device=dev)
+    t5sel = _time_loop(torch, lambda: kvp.kvp_select_topk(sc5.view(rows5, c5["T"]), k5, idx5, ws=wsel5), 10)
     M5 = c5["G"] * c5["W"]
     flops5 = 2 * 2.0 * rows5 * M5 * c5["T"] * c5["D"]
     ops["long_context_score_select"] = {
@@ -369,7 +447,7 @@ def side_measurements(kvp, workloads, torch, dev, K8, V8):
         "score_K_read_frac_hbm": round(2 * K5.numel() * 2 / t5s / 1e9 / HBM_PEAK_GBS, 4),
         "select_us": round(t5sel * 1e6, 1), "select_GBs_alg": round(rows5 * (c5["T"] + k5) * 4 / t5sel / 1e9, 1),
         "note": "scores come from kvp_score_tokens (two passes over K: both counted in score_K_read)"}
-    del K5, Q5, sc5, ws5, idx5
+    del K5, Q5, sc5, ws5, idx5, wsel5
     # --- key-only importance scores (knorm, keydiff) on the resident K plane ---
     sc8 = torch.empty(L, H, T, dtype=torch.float32, device=dev)
     wsk = torch.empty(kvp.kvp_score_keys_workspace_bytes(L, H, T, kvp.KVP_SCORE_KEYDIFF) + 16, dtype=torch.uint8, device=dev)
@@ -430,33 +508,53 @@ def side_measurements(kvp, workloads, torch, dev, K8, V8):
     k = kvp.kvp_keep_count(c["keep_ratio"], c["T"])
     s = workloads.make_scores(rows, c["T"], seed=0, device=dev)
     idx = torch.empty(rows, k, dtype=torch.int32, device=dev)
-    t_sel = _time_loop(torch, lambda: kvp.kvp_select_topk(s, k, idx), 10)
+    wsel = torch.empty(kvp.kvp_select_workspace_bytes(rows, c["T"], k), dtype=torch.uint8, device=dev)
+    t_sel = _time_loop(torch, lambda: kvp.kvp_select_topk(s, k, idx, ws=wsel), 10)
     ops["long_context_select"] = {"workload": f"{rows} rows x {c['T']} squared-normal stand-in scores, k={k}",
                                   "select_us": round(t_sel * 1e6, 1),
                                   "select_GBs_alg": round(rows * (c["T"] + k) * 4 / t_sel / 1e9, 1)}
-    del s, idx
-    # --- utility-table sweep: one context of the 64 ---
+    del s, idx, wsel
+    # --- utility-table sweep: the 64 contexts of the configuration, context i from seed i, generated on the
+    #     device; one kvp_eval_configs call per context, all enqueued on one stream with one shared workspace ---
     c = workloads.CONFIGS["utility_sweep"]
-    Ke, Ve = workloads.make_kv(c["L"], c["T"], c["H"], c["D"], seed=0, device=dev)
-    Qe = workloads.make_q(c["L"], c["W"], c["G"] * c["H"], c["D"], seed=0, device=dev)
+    n_ctx = c["n_ctx"]
+    ctxs = []
+    for i in range(n_ctx):
+        Ke, Ve = workloads.make_kv(c["L"], c["T"], c["H"], c["D"], seed=i, device=dev)
+        Qe = workloads.make_q(c["L"], c["W"], c["G"] * c["H"], c["D"], seed=i, device=dev)
+        ctxs.append((Qe, Ke, Ve))
     ks = [kvp.kvp_keep_count(r, c["T"]) for r in c["keep_ratios"]] + [c["T"]]
     variants = [(16, 0)] + [(b, g) for b in c["bits_set"] for g in c["group_set"]]
     cfgs = [(b, g, kk) for (b, g) in variants for kk in ks]
     ws = torch.empty(kvp.kvp_eval_workspace_bytes(c["L"], c["H"], c["G"] * c["H"], c["W"], c["T"], len(cfgs)),
                      dtype=torch.uint8, device=dev)
-    loss = torch.empty(len(cfgs), dtype=torch.float32, device=dev)
-    t_ev = _time_loop(torch, lambda: kvp.kvp_eval_configs(Qe, Ke, Ve, cfgs, loss=loss, ws=ws), 2)
-    t_ev_mx = _time_loop(torch, lambda: kvp.kvp_eval_configs(Qe, Ke, Ve, cfgs, loss=loss, ws=ws, pv_matrix_cores=True), 2)
+    loss = torch.empty(n_ctx, len(cfgs), dtype=torch.float32, device=dev)
+    Qe, Ke, Ve = ctxs[0]
+    t_ev = _time_loop(torch, lambda: kvp.kvp_eval_configs(Qe, Ke, Ve, cfgs, loss=loss[0], ws=ws), 2)
+    t_ev_mx = _time_loop(torch, lambda: kvp.kvp_eval_configs(Qe, Ke, Ve, cfgs, loss=loss[0], ws=ws, pv_matrix_cores=True), 2)
+
+    def sweep():
+        for i, (q_, k_, v_) in enumerate(ctxs):
+            kvp.kvp_eval_configs(q_, k_, v_, cfgs, loss=loss[i], ws=ws)
+    t_sweep = _time_loop(torch, sweep, 1, warm=1, batches=2)
     M = c["G"] * c["W"]
     # work actually done: one stream per codec, each over the largest keep-set (here all T tokens); the
     # 16-bit stream doubles as the reference
     tokens = len(variants) * max(ks)
     pv_flops = 2.0 * c["L"] * c["H"] * M * c["D"] * tokens
-    ops["utility_sweep"] = {"workload": f"1 of {c['n_ctx']} contexts: {c['L']}x{c['H']}x{c['D']}x{c['T']}, {len(cfgs)} configs",
-                            "eval_ms_per_context": round(t_ev * 1e3, 2), "configs_per_s": round(len(cfgs) / t_ev, 1),
-                            "bound": "alu", "pv_TFLOPs_fp32": round(pv_flops / t_ev / 1e12, 2),
-                            "pv_frac_valu_peak": round(pv_flops / t_ev / 1e12 / VALU_FP32_PEAK_TFLOPS, 4),
-                            "opt_in_pv_matrix_cores": {"eval_ms_per_context": round(t_ev_mx * 1e3, 2),
+    pv_rate = pv_flops * n_ctx / t_sweep / 1e12
+    ops["utility_sweep"] = {"workload": f"{n_ctx} contexts (seed i for context i) of {c['L']}x{c['H']}x{c['D']}x{c['T']}, "
+                                        f"{len(cfgs)} configs each, one call per context on one stream",
+                            "sweep_ms": round(t_sweep * 1e3, 1), "eval_ms_per_context": round(t_sweep * 1e3 / n_ctx, 2),
+                            "eval_ms_one_context_alone": round(t_ev * 1e3, 2),
+                            "configs_per_s": round(len(cfgs) * n_ctx / t_sweep, 1),
+                            "input_GBs": round(n_ctx * 2 * Ke.numel() * 2 / t_sweep / 1e9, 1),
+                            "bound": "alu", "pv_TFLOPs_fp32": round(pv_rate, 2),
+                            "pv_frac_valu_peak_no_packed_fp32": round(pv_rate / VALU_FP32_PEAK_TFLOPS, 4),
+                            "pv_frac_published_fp32_vector_peak": round(pv_rate / VALU_FP32_PUBLISHED_TFLOPS, 4),
+                            "peaks_TFLOPs": {"no_packed_fp32 (256 CU x 4 SIMD x 16 lanes x 2 flop x 2.4 GHz)": VALU_FP32_PEAK_TFLOPS,
+                                             "published (packed fp32, not used by this library)": VALU_FP32_PUBLISHED_TFLOPS},
+                            "opt_in_pv_matrix_cores": {"eval_ms_one_context_alone": round(t_ev_mx * 1e3, 2),
                                                        "configs_per_s": round(len(cfgs) / t_ev_mx, 1),
                                                        "mfma_TFLOPs": round(3 * pv_flops / t_ev_mx / 1e12, 1)}}
     return ops
@@ -500,8 +598,9 @@ def profile_only(args, kvp, workloads, torch, dev, K, V, qK, pK, bt, nb):
         s = workloads.make_scores(rows, T, seed=0, device=dev)
         k = kvp.kvp_keep_count(0.3 if args.only == "select_many" else 0.1, T)
         idx = torch.empty(rows, k, dtype=torch.int32, device=dev)
+        wsel = torch.empty(max(kvp.kvp_select_workspace_bytes(rows, T, k), 16), dtype=torch.uint8, device=dev)
         for _ in range(n):
-            kvp.kvp_select_topk(s, k, idx)
+            kvp.kvp_select_topk(s, k, idx, ws=wsel)
     elif args.only == "eval":
         c = workloads.CONFIGS["utility_sweep"]
         Ke, Ve = workloads.make_kv(c["L"], c["T"], c["H"], c["D"], seed=0, device=dev)

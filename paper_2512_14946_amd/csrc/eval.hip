@@ -595,7 +595,7 @@ size_t align256(size_t n) { return (n + 255) / 256 * 256; }
 
 struct EvalPlan {
   int64_t LH, M, RB;
-  size_t score_ws, scores, idx, shell, order, o_levels, den, num, layer, total;
+  size_t score_ws, select_ws, scores, idx, shell, order, o_levels, den, num, layer, total;
 };
 
 EvalPlan make_plan(int64_t L, int64_t Hkv, int64_t Hq, int64_t W, int64_t T, int32_t n_cfgs) {
@@ -606,6 +606,7 @@ EvalPlan make_plan(int64_t L, int64_t Hkv, int64_t Hq, int64_t W, int64_t T, int
   const int64_t cfgs = n_cfgs > 0 ? n_cfgs : 1;
   const int64_t levels = cfgs < kMaxLevels ? cfgs : kMaxLevels;
   p.score_ws = align256(kvp_score_workspace_bytes(L, Hkv, Hq, W, T));
+  p.select_ws = align256(select_workspace_bytes(p.LH, T));   // shared by the keep levels (same stream)
   p.scores = align256(static_cast<size_t>(p.LH) * T * sizeof(float));
   p.idx = align256(static_cast<size_t>(levels) * p.LH * T * sizeof(int32_t));
   p.shell = align256(static_cast<size_t>(p.LH) * T);
@@ -616,7 +617,7 @@ EvalPlan make_plan(int64_t L, int64_t Hkv, int64_t Hq, int64_t W, int64_t T, int
   p.den = align256(static_cast<size_t>(p.LH) * p.RB * sizeof(float));
   p.num = align256(static_cast<size_t>(p.LH) * p.RB * streams * levels * sizeof(float));
   p.layer = align256(static_cast<size_t>(L) * cfgs * 2 * sizeof(double));
-  p.total = p.score_ws + p.scores + p.idx + p.shell + p.order + p.o_levels + p.den + p.num + p.layer;
+  p.total = p.score_ws + p.select_ws + p.scores + p.idx + p.shell + p.order + p.o_levels + p.den + p.num + p.layer;
   return p;
 }
 
@@ -704,6 +705,7 @@ extern "C" int32_t kvp_eval_configs_ex(const kvp_view* q_win, const kvp_view* k,
   char* cursor = static_cast<char*>(ws);
   auto take = [&cursor](size_t bytes) { char* r = cursor; cursor += bytes; return r; };
   void* score_ws = take(p.score_ws);
+  void* select_ws = take(p.select_ws);
   float* scores = reinterpret_cast<float*>(take(p.scores));
   int32_t* idx = reinterpret_cast<int32_t*>(take(p.idx));
   a.shell = reinterpret_cast<uint8_t*>(take(p.shell));
@@ -727,6 +729,8 @@ extern "C" int32_t kvp_eval_configs_ex(const kvp_view* q_win, const kvp_view* k,
   a.loss = loss;
   a.partial = partial;
 
+  const int64_t items = static_cast<int64_t>(p.RB) * p.LH * a.n_streams;
+  if (items >= (1ll << 30)) return KVP_ERR_SHAPE;   // before anything is enqueued
   const hipStream_t st = as_stream(stream);
   rc = score_tokens_impl(q_win, k, 1, 1, scores, score_ws, p.score_ws, st);
   if (rc != KVP_OK) return rc;
@@ -735,13 +739,11 @@ extern "C" int32_t kvp_eval_configs_ex(const kvp_view* q_win, const kvp_view* k,
       a.level_idx[j] = nullptr;  // every token
     } else {
       int32_t* out = idx + static_cast<int64_t>(j) * p.LH * T;
-      select_topk_launch(scores, p.LH, T, T, a.level_k[j], out, st);
+      select_topk_launch(scores, p.LH, T, T, a.level_k[j], out, select_ws, st);
       a.level_idx[j] = out;
     }
   }
   build_order_kernel<<<dim3(static_cast<unsigned>(p.LH)), kOrderThreads, 0, st>>>(a);
-  const int64_t items = static_cast<int64_t>(p.RB) * p.LH * a.n_streams;
-  if (items >= (1ll << 30)) return KVP_ERR_SHAPE;
   const dim3 grid(static_cast<unsigned>(kXcds * ceil_div(items, kXcds)));
   if (flags & KVP_EVAL_PV_MATRIX_CORES) {
     attention_kernel<true><<<grid, kThreads, 0, st>>>(a);

@@ -9,9 +9,11 @@ namespace kvp {
 int32_t score_tokens_impl(const kvp_view* q_win, const kvp_view* k, int32_t causal, int32_t force_window,
                           float* scores, void* ws, size_t ws_bytes, hipStream_t st);
 
-// kvp_select_topk's kernel launch; arguments already validated, n_rows > 0, 0 < k <= T.
+// kvp_select_topk's kernel launches; arguments already validated, n_rows > 0, 0 < k <= T; ws holds at least
+// select_workspace_bytes(n_rows, T) bytes, 16-byte aligned (may be null when that is 0).
+size_t select_workspace_bytes(int64_t n_rows, int64_t T);
 void select_topk_launch(const float* scores, int64_t n_rows, int64_t T, int64_t row_stride, int64_t k,
-                        int32_t* idx_out, hipStream_t st);
+                        int32_t* idx_out, void* ws, hipStream_t st);
 
 // Validated arguments of kvp_quantize as the kernels take them.
 enum SrcMode { kLinear = 0, kStrided = 1, kPaged = 2 };

@@ -220,9 +220,18 @@ def _check(rc: int, what: str):
         raise KVPError(rc, what)
 
 
-def _workspace(ws, nbytes: int, device):
+def _workspace(ws, nbytes: int, device, stream=None):
+    """(tensor kept alive by the caller, pointer, bytes).  A workspace allocated here is a temporary: when the
+    call runs on a stream other than torch's current one, the allocator is told so that it does not hand the
+    memory out again while the kernels still use it."""
     if ws is None:
-        ws = torch.empty(max(nbytes, 16), dtype=torch.uint8, device=device)
+        if nbytes == 0:
+            return None, None, 0
+        ws = torch.empty(nbytes, dtype=torch.uint8, device=device)
+        if stream is not None:
+            s = stream if isinstance(stream, torch.cuda.Stream) else torch.cuda.ExternalStream(int(stream))
+            if s != torch.cuda.current_stream(device):
+                ws.record_stream(s)
     return ws, ws.data_ptr(), ws.numel() * ws.element_size()
 
 
@@ -293,7 +302,7 @@ def kvp_score_tokens(q_win: torch.Tensor, k: torch.Tensor, scores: torch.Tensor 
         scores = torch.empty(L, Hkv, T, dtype=torch.float32, device=k.device)
     if scores.dtype != torch.float32 or not scores.is_contiguous() or tuple(scores.shape) != (L, Hkv, T):
         raise ValueError("scores must be contiguous float32 [L][Hkv][T]")
-    ws, wp, wb = _workspace(ws, kvp_score_workspace_bytes(L, Hkv, Hq, W, T), k.device)
+    ws, wp, wb = _workspace(ws, kvp_score_workspace_bytes(L, Hkv, Hq, W, T), k.device, stream)
     qv, kv = _view(q_win), _view(k)
     _check(_lib.kvp_score_tokens(ctypes.byref(qv), ctypes.byref(kv), int(causal), int(force_window),
                                  scores.data_ptr(), wp, wb, _stream(stream)), "kvp_score_tokens")
@@ -333,7 +342,7 @@ def kvp_score_keys(k: torch.Tensor, method: int, scores: torch.Tensor | None = N
         scores = torch.empty(L, H, T, dtype=torch.float32, device=k.device)
     if scores.dtype != torch.float32 or not scores.is_contiguous() or tuple(scores.shape) != (L, H, T):
         raise ValueError("scores must be contiguous float32 [L][H][T]")
-    ws, wp, wb = _workspace(ws, kvp_score_keys_workspace_bytes(L, H, T, method), k.device)
+    ws, wp, wb = _workspace(ws, kvp_score_keys_workspace_bytes(L, H, T, method), k.device, stream)
     kv = _view(k)
     _check(_lib.kvp_score_keys(ctypes.byref(kv), int(method), scores.data_ptr(), wp, wb, _stream(stream)),
            "kvp_score_keys")
@@ -356,7 +365,7 @@ def kvp_select_topk(scores: torch.Tensor, k: int, idx_out: torch.Tensor | None =
         idx_out = torch.empty(n_rows, k, dtype=torch.int32, device=scores.device)
     if idx_out.dtype != torch.int32 or not idx_out.is_contiguous() or tuple(idx_out.shape) != (n_rows, k):
         raise ValueError("idx_out must be contiguous int32 [n_rows][k]")
-    ws, wp, wb = _workspace(ws, kvp_select_workspace_bytes(n_rows, T, k), scores.device)
+    ws, wp, wb = _workspace(ws, kvp_select_workspace_bytes(n_rows, T, k), scores.device, stream)
     _check(_lib.kvp_select_topk(scores.data_ptr(), n_rows, T, row_stride, k, idx_out.data_ptr(), wp, wb,
                                 _stream(stream)), "kvp_select_topk")
     return idx_out
@@ -399,7 +408,7 @@ def kvp_eval_configs(q_win: torch.Tensor, k: torch.Tensor, v: torch.Tensor, cfgs
         loss = torch.empty(n, dtype=torch.float32, device=k.device)
     if want_partial and partial is None:
         partial = torch.empty(L, n, 2, dtype=torch.float32, device=k.device)
-    ws, wp, wb = _workspace(ws, kvp_eval_workspace_bytes(L, Hkv, Hq, W, T, n), k.device)
+    ws, wp, wb = _workspace(ws, kvp_eval_workspace_bytes(L, Hkv, Hq, W, T, n), k.device, stream)
     qv, kv, vv = _view(q_win), _view(k), _view(v)
     pp = partial.data_ptr() if partial is not None else None
     if pv_matrix_cores:

@@ -83,6 +83,68 @@ def test_topk_long_rows_many_ties():
     _check_topk(s, T - 5)
 
 
+def _long_rows(T, seed):
+    """Rows that take every branch of the split-row path: plain random scores, few ties, heavy ties at the
+    threshold (more candidates than a span's slice holds: the row is redone by the streaming kernel), one value
+    only, sorted both ways, negative scores with signed zeros, a forced +inf window."""
+    s = workloads.make_scores(9, T, seed=seed).numpy()
+    s[1] = np.round(s[1] * 64) / 64                                   # a few hundred levels
+    s[2] = np.round(s[2] * 2) / 2                                     # a handful of levels: huge tie classes
+    s[3] = 0.25                                                       # all equal
+    s[4] = np.sort(s[4])                                              # ascending: the kept tokens are the last ones
+    s[5] = np.sort(s[5])[::-1]                                        # descending
+    s[6] = -s[6]
+    s[6, ::5] = 0.0
+    s[6, 1::5] = -0.0
+    s[7, T - 64:] = np.inf
+    s[8, : T // 2] = 1e-30                                            # half the row in one bin, far below the rest
+    return s
+
+
+@pytest.mark.parametrize("T", [16385, 20000, 49999, 131072 + 5])
+def test_topk_split_rows(T):
+    _say("topk split rows", T)
+    s = _long_rows(T, seed=T)
+    for k in sorted({1, 7, T // 10, T // 2 + 1, T - T // 10, T - 1, T}):
+        _check_topk(s, k)
+
+
+def test_topk_split_rows_strided_unaligned_and_many_rows():
+    _say("topk split rows strided")
+    kvp = _kvp()
+    T = 33001
+    base = workloads.make_scores(70, T + 30, seed=11).to(DEV)
+    view = base[:, 1:T + 1]                                           # rows neither 16-byte aligned nor contiguous
+    got = kvp.kvp_select_topk(view, 9000)
+    torch.cuda.synchronize()
+    assert np.array_equal(got.cpu().numpy(), oracle.select_topk(base.cpu().numpy()[:, 1:T + 1], 9000))
+
+
+def test_topk_rows_beyond_the_split_limit():
+    _say("topk 2^20 + 3")
+    T = (1 << 20) + 3
+    s = workloads.make_scores(2, T, seed=12).numpy()
+    s[1] = np.round(s[1] * 16) / 16
+    _check_topk(s, T // 7)
+
+
+def test_topk_workspace_is_validated():
+    kvp = _kvp()
+    T = 40000
+    s = workloads.make_scores(3, T, seed=1).to(DEV)
+    need = kvp.kvp_select_workspace_bytes(3, T, 100)
+    assert need > 0 and kvp.kvp_select_workspace_bytes(3, 16384, 100) == 0
+    with pytest.raises(kvp.KVPError) as e:
+        kvp.kvp_select_topk(s, 100, ws=torch.empty(need - 256, dtype=torch.uint8, device=DEV))
+    assert e.value.code == -5
+    # a caller-owned workspace, reused across calls with different k
+    ws = torch.empty(need, dtype=torch.uint8, device=DEV)
+    for k in (100, 20000):
+        got = kvp.kvp_select_topk(s, k, ws=ws)
+        torch.cuda.synchronize()
+        assert np.array_equal(got.cpu().numpy(), oracle.select_topk(s.cpu().numpy(), k))
+
+
 def test_topk_errors():
     kvp = _kvp()
     s = torch.zeros(2, 10, device=DEV)
