@@ -181,7 +181,11 @@ size_t kvp_score_keys_workspace_bytes(int64_t L, int64_t H, int64_t T, int32_t m
  * of n_rows rows of T fp32 scores (row_stride floats apart): the indices of the
  * k largest, equal scores resolved toward the lowest index, written ascending
  * to idx_out [n_rows][k] (device int32).  NaN scores are out of contract.
- * 0 <= k <= T; T < 2^31. */
+ * 0 <= k <= T; T < 2^30.  Rows longer than 16384 and up to 2^18 scores are split over several
+ * workgroups and need scratch: kvp_select_workspace_bytes(n_rows, T, k) bytes (16 bytes for two
+ * pivots and a flag per row, two counts per 16384-score span, 64 KiB of candidate slots per
+ * row), 16-byte aligned; it returns 0 for other lengths, for which ws may be NULL.  A missing
+ * or short workspace: KVP_ERR_WORKSPACE. */
 int32_t kvp_select_topk(const float* scores, int64_t n_rows, int64_t T, int64_t row_stride, int64_t k,
                         int32_t* idx_out, void* ws, size_t ws_bytes, void* stream);
 size_t kvp_select_workspace_bytes(int64_t n_rows, int64_t T, int64_t k);
