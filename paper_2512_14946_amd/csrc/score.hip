@@ -7,7 +7,8 @@
 // (v_mfma_f32_32x32x16_bf16, fp32 accumulate), because a softmax row must be normalized before it
 // can be summed into a column:
 //   pass A  row statistics: running max and sum of exponentials per window row, per key chunk;
-//   combine per-row bias b_r = max_r + log2(sum_r) over all chunks (tiny kernel);
+//   combine per-row bias b_r = max_r + log2(sum_r) over all chunks (a tiny kernel, or the prologue of pass B
+//           when there are few chunks);
 //   pass B  column sums: scores[t] = sum_r 2^(s_rt - b_r).
 // Logits are kept in the base-2 domain (s = q.k * log2(e)/sqrt(D)) so the exponential is one
 // v_exp_f32.
@@ -51,9 +52,10 @@ struct ScoreArgs {
   int64_t q_sl, q_st, q_sh;
   const uint16_t* k;
   int64_t k_sl, k_st, k_sh;
-  int32_t T, W, G, Hkv, M, Mrows;           // Mrows = 32 * (query tiles, rounded up to a power of two)
+  int32_t T, W, G, Hkv, M, Mrows, nqt;      // nqt = query tiles in use (1 .. 16); Mrows = 32 * nqt
   int32_t chunk_keys, n_chunks;
   int32_t causal, force_window;
+  int32_t fold_combine;                     // pass B combines the chunk statistics itself (few chunks: saves a launch)
   float scale2;                             // log2(e) / sqrt(D)
   float2* partial;                          // [L*Hkv][n_chunks][Mrows] (max, sum) in the base-2 domain
   float* bias;                              // [L*Hkv][Mrows]
@@ -83,6 +85,20 @@ __device__ __forceinline__ void load_key_tile(const ScoreArgs& a, const uint16_t
   }
 }
 
+// bias_r = max_r + log2(sum_r) over all key chunks of (layer, head) lh; +inf for padding rows (they then contribute 0).
+__device__ __forceinline__ float combined_bias(const ScoreArgs& a, int lh, int r) {
+  if (r >= a.M) return INFINITY;
+  const float2* part = a.partial + static_cast<int64_t>(lh) * a.n_chunks * a.Mrows + r;
+  float m = -INFINITY;
+  for (int c = 0; c < a.n_chunks; ++c) m = fmaxf(m, part[static_cast<int64_t>(c) * a.Mrows].x);
+  float z = 0.0f;
+  for (int c = 0; c < a.n_chunks; ++c) {
+    const float2 p = part[static_cast<int64_t>(c) * a.Mrows];
+    if (p.x != -INFINITY) z += p.y * __builtin_amdgcn_exp2f(p.x - m);
+  }
+  return m + __builtin_amdgcn_logf(z);  // v_log_f32 is log2
+}
+
 template <int NQT, bool PASS_B>
 __global__ __launch_bounds__((PASS_B ? kWavesB : kWavesA) * kWave, 2) void score_kernel(const ScoreArgs a) {
   constexpr int kWavesPerBlock = PASS_B ? kWavesB : kWavesA;
@@ -100,7 +116,7 @@ __global__ __launch_bounds__((PASS_B ? kWavesB : kWavesA) * kWave, 2) void score
   const int win0 = a.T - a.W;  // first window position
 
   // ---- stage the window queries of this (layer, kv head): row r = u * W + w, zeros beyond M ----
-  for (int idx = threadIdx.x; idx < NQT * 32 * 16; idx += kThreads) {
+  for (int idx = threadIdx.x; idx < a.Mrows * 16; idx += kThreads) {
     const int r = idx >> 4, part = idx & 15;
     uint4 v = make_uint4(0, 0, 0, 0);
     if (r < a.M) {
@@ -110,10 +126,10 @@ __global__ __launch_bounds__((PASS_B ? kWavesB : kWavesA) * kWave, 2) void score
     }
     *reinterpret_cast<uint4*>(q_s + r * kPitch + part * 8) = v;
   }
-  for (int r = threadIdx.x; r < NQT * 32; r += kThreads) {
+  for (int r = threadIdx.x; r < a.Mrows; r += kThreads) {
     wpos_s[r] = r % a.W;
     // rows beyond M carry +inf: they contribute 2^-inf = 0
-    if constexpr (PASS_B) bias_s[r] = a.bias[static_cast<int64_t>(lh) * a.Mrows + r];
+    if constexpr (PASS_B) bias_s[r] = a.fold_combine ? combined_bias(a, lh, r) : a.bias[static_cast<int64_t>(lh) * a.Mrows + r];
   }
   __syncthreads();
 
@@ -200,65 +216,58 @@ __global__ __launch_bounds__((PASS_B ? kWavesB : kWavesA) * kWave, 2) void score
 
   // One 32-key tile against all query tiles as a software pipeline over the query tiles:
   //   step n:  LDS operand reads of tile n+2, then  MFMAs of tile n+1  |  vector-ALU work of tile n.
+  // Query tiles in use.  Pass A is instantiated for the exact count (its per-tile statistics live in registers with
+  // static indices), pass B for 1, 2, 4, 8 or 16 tiles of LDS with the count in use as a run-time value.
+  const int nqt = PASS_B ? a.nqt : NQT;
   auto key_tile = [&](auto masked_tag, const uint4 kop[8], int tk0) {
     bf16x8 qop_a[8], qop_b[8];
     floatx16 acc_a, acc_b;
     float col = 0.0f, dummy_m = 0.0f, dummy_z = 0.0f;  // pass B: this lane's key column
-    auto finish_column = [&]() {
-      if constexpr (PASS_B) {
-        col += __shfl_xor(col, 32, 64);
-        const int t = tk0 + lane;
-        if (lane < 32 && t < a.T)
-          a.scores[static_cast<int64_t>(lh) * a.T + t] = (a.force_window && t >= win0) ? INFINITY : col;
-      }
-    };
     q_operand(0, qop_a);
     acc_a = mfma_tile(kop, qop_a);
-    if constexpr (NQT == 1) {
-      consume(masked_tag, acc_a, 0, tk0, col, run_m[0], run_z[0]);
-      finish_column();
-    } else {
-      q_operand(1, qop_b);
-      if constexpr (!PASS_B) {
-        // the per-tile running statistics need static register indices: fully unrolled
+    if (nqt > 1) q_operand(1, qop_b);
+    // two pipeline steps: tile qt is finished in acc_a, the operands of tile qt+1 are in qop_b, tile qt+2 exists
+    auto two_steps = [&](int qt, float& m0, float& z0, float& m1, float& z1) {
+      q_operand(qt + 2, qop_a);
+      pin();
+      acc_b = mfma_tile(kop, qop_b);
+      consume(masked_tag, acc_a, qt, tk0, col, m0, z0);
+      pin();
+      if (qt + 3 < nqt) q_operand(qt + 3, qop_b);
+      pin();
+      acc_a = mfma_tile(kop, qop_a);
+      consume(masked_tag, acc_b, qt + 1, tk0, col, m1, z1);
+      pin();
+    };
+    if constexpr (!PASS_B) {
+      // fully unrolled: static register indices for the running statistics
 #pragma unroll
-        for (int qt = 0; qt + 2 < NQT; qt += 2) {
-          q_operand(qt + 2, qop_a);
-          pin();
-          acc_b = mfma_tile(kop, qop_b);
-          consume(masked_tag, acc_a, qt, tk0, col, run_m[qt], run_z[qt]);
-          pin();
-          q_operand(qt + 3, qop_b);
-          pin();
-          acc_a = mfma_tile(kop, qop_a);
-          consume(masked_tag, acc_b, qt + 1, tk0, col, run_m[qt + 1], run_z[qt + 1]);
-          pin();
-        }
+      for (int qt = 0; qt + 2 < NQT; qt += 2) two_steps(qt, run_m[qt], run_z[qt], run_m[qt + 1], run_z[qt + 1]);
+      if constexpr (NQT % 2 == 0) {
         acc_b = mfma_tile(kop, qop_b);
         consume(masked_tag, acc_a, NQT - 2, tk0, col, run_m[NQT - 2], run_z[NQT - 2]);
         pin();
         consume(masked_tag, acc_b, NQT - 1, tk0, col, run_m[NQT - 1], run_z[NQT - 1]);
       } else {
-        // no per-tile state: a rolled loop keeps the register footprint independent of the tile count
-#pragma unroll 1
-        for (int qt = 0; qt + 2 < NQT; qt += 2) {
-          q_operand(qt + 2, qop_a);
-          pin();
-          acc_b = mfma_tile(kop, qop_b);
-          consume(masked_tag, acc_a, qt, tk0, col, dummy_m, dummy_z);
-          pin();
-          q_operand(qt + 3, qop_b);
-          pin();
-          acc_a = mfma_tile(kop, qop_a);
-          consume(masked_tag, acc_b, qt + 1, tk0, col, dummy_m, dummy_z);
-          pin();
-        }
-        acc_b = mfma_tile(kop, qop_b);
-        consume(masked_tag, acc_a, NQT - 2, tk0, col, dummy_m, dummy_z);
-        pin();
-        consume(masked_tag, acc_b, NQT - 1, tk0, col, dummy_m, dummy_z);
-        finish_column();
+        consume(masked_tag, acc_a, NQT - 1, tk0, col, run_m[NQT - 1], run_z[NQT - 1]);
       }
+    } else {
+      // no per-tile state: a rolled loop keeps the register footprint independent of the tile count
+      int qt = 0;
+#pragma unroll 1
+      for (; qt + 2 < nqt; qt += 2) two_steps(qt, dummy_m, dummy_z, dummy_m, dummy_z);
+      if (qt + 1 < nqt) {
+        acc_b = mfma_tile(kop, qop_b);
+        consume(masked_tag, acc_a, qt, tk0, col, dummy_m, dummy_z);
+        pin();
+        consume(masked_tag, acc_b, qt + 1, tk0, col, dummy_m, dummy_z);
+      } else {
+        consume(masked_tag, acc_a, qt, tk0, col, dummy_m, dummy_z);
+      }
+      col += __shfl_xor(col, 32, 64);
+      const int t = tk0 + lane;
+      if (lane < 32 && t < a.T)
+        a.scores[static_cast<int64_t>(lh) * a.T + t] = (a.force_window && t >= win0) ? INFINITY : col;
     }
   };
 
@@ -299,7 +308,7 @@ __global__ __launch_bounds__((PASS_B ? kWavesB : kWavesA) * kWave, 2) void score
       if (lane < 32) merge_s[wave * (NQT * 32) + qt * 32 + lane] = make_float2(m_new, z);
     }
     __syncthreads();
-    for (int r = threadIdx.x; r < NQT * 32; r += kThreads) {
+    for (int r = threadIdx.x; r < a.Mrows; r += kThreads) {
       float m = -INFINITY;
 #pragma unroll
       for (int w = 0; w < kWavesPerBlock; ++w) m = fmaxf(m, merge_s[w * (NQT * 32) + r].x);
@@ -315,24 +324,10 @@ __global__ __launch_bounds__((PASS_B ? kWavesB : kWavesA) * kWave, 2) void score
   }
 }
 
-// bias_r = max_r + log2(sum_r) over all key chunks; +inf for padding rows (they then contribute 0).
+// The same combination as its own launch, once per (layer, head), when there are many chunks.
 __global__ void combine_kernel(const ScoreArgs a) {
   const int lh = blockIdx.x;
-  for (int r = threadIdx.x; r < a.Mrows; r += blockDim.x) {
-    float b = INFINITY;
-    if (r < a.M) {
-      float m = -INFINITY;
-      for (int c = 0; c < a.n_chunks; ++c)
-        m = fmaxf(m, a.partial[(static_cast<int64_t>(lh) * a.n_chunks + c) * a.Mrows + r].x);
-      float z = 0.0f;
-      for (int c = 0; c < a.n_chunks; ++c) {
-        const float2 p = a.partial[(static_cast<int64_t>(lh) * a.n_chunks + c) * a.Mrows + r];
-        if (p.x != -INFINITY) z += p.y * __builtin_amdgcn_exp2f(p.x - m);
-      }
-      b = m + __builtin_amdgcn_logf(z);  // v_log_f32 is log2
-    }
-    a.bias[static_cast<int64_t>(lh) * a.Mrows + r] = b;
-  }
+  for (int r = threadIdx.x; r < a.Mrows; r += blockDim.x) a.bias[static_cast<int64_t>(lh) * a.Mrows + r] = combined_bias(a, lh, r);
 }
 
 // Keys per block: large chunks amortize the query staging, small ones fill the chip.
@@ -350,8 +345,7 @@ struct ScorePlan {
 ScorePlan make_plan(int64_t L, int64_t Hkv, int64_t Hq, int64_t W, int64_t T) {
   ScorePlan p{};
   p.M = static_cast<int32_t>((Hq / Hkv) * W);
-  p.nqt = 1;
-  while (p.nqt * 32 < p.M) p.nqt *= 2;
+  p.nqt = (p.M + 31) / 32;              // query tiles in use (1 .. 16)
   p.Mrows = p.nqt * 32;
   p.chunk_keys = choose_chunk_keys(L * Hkv, T);
   p.n_chunks = static_cast<int32_t>(ceil_div(T, p.chunk_keys));
@@ -361,16 +355,23 @@ ScorePlan make_plan(int64_t L, int64_t Hkv, int64_t Hq, int64_t W, int64_t T) {
   return p;
 }
 
-template <bool PASS_B>
-void launch_pass(int nqt, dim3 grid, hipStream_t st, const ScoreArgs& a) {
-  constexpr int threads = (PASS_B ? kWavesB : kWavesA) * kWave;
-  switch (nqt) {
-    case 1: score_kernel<1, PASS_B><<<grid, threads, 0, st>>>(a); break;
-    case 2: score_kernel<2, PASS_B><<<grid, threads, 0, st>>>(a); break;
-    case 4: score_kernel<4, PASS_B><<<grid, threads, 0, st>>>(a); break;
-    case 8: score_kernel<8, PASS_B><<<grid, threads, 0, st>>>(a); break;
-    default: score_kernel<16, PASS_B><<<grid, threads, 0, st>>>(a); break;
+// Pass A is instantiated for every tile count 1 .. 16, pass B for 1, 2, 4, 8 and 16 tiles of LDS (M = 224 runs
+// 7 tiles in the 8-tile instantiation).
+template <int N>
+void launch_pass_a(int nqt, dim3 grid, hipStream_t st, const ScoreArgs& a) {
+  if constexpr (N <= 16) {
+    if (nqt == N) score_kernel<N, false><<<grid, kWavesA * kWave, 0, st>>>(a);
+    else launch_pass_a<N + 1>(nqt, grid, st, a);
   }
+}
+
+void launch_pass_b(int nqt, dim3 grid, hipStream_t st, const ScoreArgs& a) {
+  constexpr int threads = kWavesB * kWave;
+  if (nqt <= 1) score_kernel<1, true><<<grid, threads, 0, st>>>(a);
+  else if (nqt <= 2) score_kernel<2, true><<<grid, threads, 0, st>>>(a);
+  else if (nqt <= 4) score_kernel<4, true><<<grid, threads, 0, st>>>(a);
+  else if (nqt <= 8) score_kernel<8, true><<<grid, threads, 0, st>>>(a);
+  else score_kernel<16, true><<<grid, threads, 0, st>>>(a);
 }
 
 }  // namespace
@@ -397,7 +398,7 @@ int32_t score_tokens_impl(const kvp_view* q_win, const kvp_view* k, int32_t caus
   a.k = static_cast<const uint16_t*>(k->ptr);
   a.k_sl = k->stride_l; a.k_st = k->stride_t; a.k_sh = k->stride_h;
   a.T = static_cast<int32_t>(T); a.W = static_cast<int32_t>(W); a.G = static_cast<int32_t>(Hq / Hkv);
-  a.Hkv = static_cast<int32_t>(Hkv); a.M = p.M; a.Mrows = p.Mrows;
+  a.Hkv = static_cast<int32_t>(Hkv); a.M = p.M; a.Mrows = p.Mrows; a.nqt = p.nqt;
   a.chunk_keys = p.chunk_keys; a.n_chunks = p.n_chunks;
   a.causal = causal ? 1 : 0; a.force_window = force_window ? 1 : 0;
   a.scale2 = kLog2e / sqrtf(static_cast<float>(kHeadDim));
@@ -406,9 +407,12 @@ int32_t score_tokens_impl(const kvp_view* q_win, const kvp_view* k, int32_t caus
   a.scores = scores;
 
   const dim3 grid(static_cast<unsigned>(p.n_chunks), static_cast<unsigned>(L * Hkv));
-  launch_pass<false>(p.nqt, grid, st, a);
-  combine_kernel<<<dim3(static_cast<unsigned>(L * Hkv)), 256, 0, st>>>(a);
-  launch_pass<true>(p.nqt, grid, st, a);
+  // With few chunks every pass-B block combines the chunk statistics of its (layer, head) itself (a few KiB of
+  // reads from the cache): a call is two launches, which is what counts for small, launch-bound shapes.
+  a.fold_combine = p.n_chunks <= 16 ? 1 : 0;
+  launch_pass_a<1>(p.nqt, grid, st, a);
+  if (!a.fold_combine) combine_kernel<<<dim3(static_cast<unsigned>(L * Hkv)), 256, 0, st>>>(a);
+  launch_pass_b(p.nqt, grid, st, a);
   return launch_status();
 }
 
