@@ -2,10 +2,9 @@
  * kvp.h -- C ABI of libkvp: the KV-cache compress / decompress hot path of
  * EvicPress (arxiv 2512.14946) on one MI355X (gfx950).
  *
- * The paper's system compresses the KV cache of a context "into multiple
- * versions" with different methods and ratios, scores every version, and on a
- * cache hit loads the chosen version back into the serving engine's paged GPU
- * memory (System design: profiler module, utility function; Implementation:
+ * The paper's system keeps several compressed versions of a context's KV cache
+ * (different methods and ratios), scores every version, and on a cache hit
+ * loads the chosen version back into the serving engine's paged GPU memory (System design: profiler module, utility function; Implementation:
  * lookup / retrieve / store / manage).  This library is the data-parallel part
  * of that: quantize, dequantize into pages, score tokens, select a keep-set,
  * and evaluate a quality-loss proxy for every candidate configuration.
@@ -53,8 +52,8 @@ typedef struct {
 } kvp_view;
 
 /* Paged bf16 plane (K or V) in the serving engine's page pool (Background:
- * PagedAttention's page-like blocks; Implementation: retrieve puts the KV
- * cache "into the paged GPU memory").  Token t of layer l lives at
+ * PagedAttention's page-like blocks; Implementation: retrieve fills the
+ * engine's paged GPU memory).  Token t of layer l lives at
  * pool[l][block_table[t / bs]][t % bs][h][:].  One block table per context,
  * shared by all layers.  Entries must lie in [0, num_blocks). */
 typedef struct {
@@ -93,10 +92,10 @@ typedef struct {
   int64_t keep_k;
 } kvp_config;
 
-/* Group-wise symmetric quantization (Background, "KV cache compression":
- * quantization "reduces the bit-width representation of KV entries"; Related
- * work: uniform quantization; Limitations: pool "that combines both token
- * dropping and quantization").  For every group of `group` consecutive channels
+/* Group-wise symmetric quantization (Background, KV cache compression: the
+ * quantization category stores KV entries at a lower bit width; Related work:
+ * uniform quantization; Limitations: a method pool that joins token dropping
+ * with quantization).  For every group of `group` consecutive channels
  * of one token's head vector:
  *     scale = max|x| / qmax   (qmax = 2^(bits-1) - 1; IEEE binary32 division)
  *     code  = clamp(rint(x / scale), -qmax, qmax)   (binary32 division,
@@ -112,39 +111,46 @@ typedef struct {
  * kvp_dequantize_paged then returns bf16_rne(fl32(fl32(code * scale) + mn)).
  * With dst->group_axis == KVP_GROUP_TOKENS the same formulas apply to groups of dst->group slots
  * of one channel (Related work: KIVI / KVQuant style per-channel key quantizers); group is 32, 64
- * or 128 slots, slots being kept tokens when keep_idx is given. */
+ * or 128 slots, slots being kept tokens when keep_idx is given.
+ * Limits: D = 128; L <= 65535; T, Tp * H and num_blocks below 2^31.  Entries of keep_idx and of a source
+ * block table that lie outside their range are clamped into it (the call cannot fault on them; the slots
+ * they feed are then meaningless): KVP_ERR_SHAPE is for sizes, not for table contents, which stay on the device. */
 int32_t kvp_quantize(const kvp_view* src, const kvp_paged* src_paged, const int32_t* keep_idx, int64_t k,
                      const kvp_qplane* dst, void* stream);
 
 /* Inverse direction, into the paged pool (Background: quantization methods
- * "have a decompression overhead"; Implementation: retrieve).  For t < src->T:
+ * pay a decompression step; Implementation: retrieve).  For t < src->T:
  *     pool[l][block_table[t/bs]][t%bs][h][c] = bf16_rne((float)code * scale)
  * (one binary32 multiply, then round-to-nearest-even to bf16).  Page slots at
  * or beyond T and blocks the table does not name are not written.  dst->T
  * must equal src->T; L, H, D must match.  Planes grouped along tokens
  * (KVP_GROUP_TOKENS) need src->group to be a multiple of dst->bs, so that a
- * page lies inside one group (KVP_ERR_UNSUPPORTED otherwise). */
+ * page lies inside one group (KVP_ERR_UNSUPPORTED otherwise).
+ * Limits: D = 128; L <= 65535; T, bs * H and num_blocks below 2^31.  Block-table entries outside
+ * [0, num_blocks) are clamped into it, as in kvp_quantize. */
 int32_t kvp_dequantize_paged(const kvp_qplane* src, const kvp_paged* dst, void* stream);
 
 /* Restore of a dropped-and-quantized plane at the ORIGINAL token positions (Limitations: the pool
- * "that combines both token dropping and quantization"; Implementation: retrieve into paged GPU
- * memory).  src holds k = src->T slots per head, written by kvp_quantize with the same keep_idx
+ * that joins token dropping with quantization; Implementation: retrieve into paged GPU memory).  src holds k = src->T slots per head, written by kvp_quantize with the same keep_idx
  * (device int32 [L][H][k], values in [0, dst->T)); slot i of head h is dequantized as in
  * kvp_dequantize_paged and stored at token t = keep_idx[l][h][i] of the pool, which spans
  * dst->T >= k tokens:  pool[l][block_table[t/bs]][t%bs][h][:].  Rows of dropped tokens are not
- * written.  keep_idx doubles as the position ids of the restored rows. */
+ * written.  keep_idx doubles as the position ids of the restored rows.  Limits as for
+ * kvp_dequantize_paged; keep_idx entries outside [0, dst->T) are clamped into it. */
 int32_t kvp_dequantize_paged_scatter(const kvp_qplane* src, const int32_t* keep_idx, const kvp_paged* dst,
                                      void* stream);
 
-/* Attention-score token importance (Evaluation, Baselines: snapkv "computes
- * the cross attention between tokens near the query and the earlier
- * contexts").  q_win is [L][W][Hq][D]: the queries of the last W positions
+/* Attention-score token importance (Evaluation, Baselines: snapkv scores the
+ * earlier context by the attention it receives from the tokens next to the
+ * query).  q_win is [L][W][Hq][D]: the queries of the last W positions
  * (T-W .. T-1) of the context; k is [L][T][Hkv][D]; G = Hq / Hkv query heads
  * share kv head h (heads h*G .. h*G+G-1).  For each (l, h):
  *     scores[l][h][t] = sum over the G*W window rows of softmax_t(q.k / sqrt(D))
  * with keys after a row's own position masked when `causal`, and positions
  * t >= T-W set to +inf when `force_window` (window tokens are always kept).
- * bf16 inputs, fp32 accumulation.  scores is device fp32 [L][Hkv][T]. */
+ * bf16 inputs, fp32 accumulation.  scores is device fp32 [L][Hkv][T].
+ * Limits: D = 128; G * W <= 512 window rows per kv head (KVP_ERR_UNSUPPORTED beyond); L * Hkv <= 65535;
+ * W <= T < 2^30 (KVP_ERR_SHAPE). */
 int32_t kvp_score_tokens(const kvp_view* q_win, const kvp_view* k, int32_t causal, int32_t force_window,
                          float* scores, void* ws, size_t ws_bytes, void* stream);
 size_t kvp_score_workspace_bytes(int64_t L, int64_t Hkv, int64_t Hq, int64_t W, int64_t T);
@@ -176,8 +182,8 @@ enum { KVP_SCORE_KNORM = 0, KVP_SCORE_KEYDIFF = 1 };
 int32_t kvp_score_keys(const kvp_view* k, int32_t method, float* scores, void* ws, size_t ws_bytes, void* stream);
 size_t kvp_score_keys_workspace_bytes(int64_t L, int64_t H, int64_t T, int32_t method);
 
-/* Per-row top-k keep-set (Evaluation, Baselines: tokens "with low
- * cross-attention scores" are dropped; IMPRESS keeps the top X%).  For each
+/* Per-row top-k keep-set (Evaluation, Baselines: the tokens with the lowest
+ * attention scores are dropped; IMPRESS keeps the top X %).  For each
  * of n_rows rows of T fp32 scores (row_stride floats apart): the indices of the
  * k largest, equal scores resolved toward the lowest index, written ascending
  * to idx_out [n_rows][k] (device int32).  NaN scores are out of contract.
@@ -204,9 +210,9 @@ int32_t kvp_smooth_scores(const float* scores, int64_t n_rows, int64_t T, int64_
                           int32_t kernel, int32_t mode, float* out, int64_t out_stride, void* stream);
 
 /* Quality-loss proxy for every candidate configuration of ONE context
- * (System design, profiler module: the KV cache is compressed "with different
- * methods and ratios" and every version is scored; utility function: the
- * quality term).  For config c = (bits, group, keep_k):
+ * (System design, profiler module: every KV cache is compressed with each
+ * method and ratio of the pool and every version is scored; utility function:
+ * the quality term).  For config c = (bits, group, keep_k):
  *     O_full = softmax(Q K^T / sqrt(D)) V          (causal, the W window rows)
  *     O_c    = the same with K, V replaced by dequantize(quantize(.)) at
  *              (bits, group) and the keys restricted to the top-keep_k keep-set
@@ -215,7 +221,7 @@ int32_t kvp_smooth_scores(const float* scores, int64_t n_rows, int64_t T, int64_
  * sums over layers, query heads, window rows and channels.  cfgs is a HOST
  * array; loss is device fp32 [n_cfgs]; partial is NULL or device fp32
  * [L][n_cfgs][2] = (numerator, denominator) per layer.  At most 64 configurations and 8 distinct
- * keep_k values per call.  The workspace holds the scores, the keep lists and one fp32 output
+ * keep_k values per call (KVP_ERR_UNSUPPORTED beyond), and the limits of kvp_score_tokens.  The workspace holds the scores, the keep lists and one fp32 output
  * (64 KiB per 128 window rows) per (layer, kv head, distinct codec, keep level): about 1.5 GB for
  * 40 configurations of a 32-layer, 8-kv-head context; ask kvp_eval_workspace_bytes. */
 int32_t kvp_eval_configs(const kvp_view* q_win, const kvp_view* k, const kvp_view* v, const kvp_config* cfgs,
@@ -232,6 +238,23 @@ enum { KVP_EVAL_PV_MATRIX_CORES = 1 };
 int32_t kvp_eval_configs_ex(const kvp_view* q_win, const kvp_view* k, const kvp_view* v, const kvp_config* cfgs,
                             int32_t n_cfgs, float* loss, float* partial, void* ws, size_t ws_bytes, uint32_t flags,
                             void* stream);
+
+/* One sizing call for every entry point that takes (ws, ws_bytes): the bytes the call needs for the
+ * sizes in `dims` (fields an operation does not use are ignored), 0 if it needs none or the sizes
+ * are invalid.  The kvp_*_workspace_bytes helpers above return the same numbers. */
+enum {
+  KVP_WS_SCORE_TOKENS = 0, /* L, Hkv, Hq, W, T */
+  KVP_WS_SCORE_KEYS = 1,   /* L, Hkv (= H), T, method */
+  KVP_WS_SELECT_TOPK = 2,  /* n_rows, T, k */
+  KVP_WS_EVAL_CONFIGS = 3  /* L, Hkv, Hq, W, T, n_cfgs */
+};
+typedef struct {
+  int64_t L, Hkv, Hq, W, T; /* layers, kv heads, query heads, window rows, tokens */
+  int64_t n_rows, k;        /* kvp_select_topk */
+  int32_t n_cfgs;           /* kvp_eval_configs */
+  int32_t method;           /* kvp_score_keys */
+} kvp_dims;
+size_t kvp_workspace_bytes(int32_t op, const kvp_dims* dims);
 
 /* ---- policy layer on the HOST (all pointers below are host pointers; no kernel is launched) ----
  *
@@ -257,7 +280,10 @@ typedef struct {
  * bytes, then lowest index, among equals).  Then every bounded tier, first to last, is brought
  * under its capacity by repeatedly applying the operation with the least utility drop among: re-
  * compressing a cache on the tier to a configuration with fewer bytes, or evicting it unchanged to
- * the next tier (ties: lowest context, compress before evict, lowest configuration).
+ * the next tier (ties: lowest context, compress before evict, lowest configuration).  This is the
+ * appendix algorithm's pair of single operations; the wider option set of the selection-module text
+ * (any method and ratio combined with a move to any lower tier in one step) is not searched, and a
+ * cache is never deleted: eviction moves it one tier down.
  * bytes, quality: [n_ctx][n_cfg]; frequency: [n_ctx]; ctx_tier (-1 = not stored) and ctx_cfg:
  * [n_ctx], updated in place.  The operations are written to ops (at most max_ops) and counted in
  * *n_ops.  KVP_ERR_SHAPE if the last tier is bounded and cannot be made to fit;
@@ -277,7 +303,8 @@ int32_t kvp_copy_bytes(void* dst, const void* src, size_t nbytes, void* stream);
 
 const char* kvp_strerror(int32_t code);
 /* 0x00MMmmpp.  1.3: kvp_qplane carries mins and group_axis; scatter restore, score smoothing and
- * kvp_eval_configs_ex exist. */
+ * kvp_eval_configs_ex exist.  1.4: kvp_select_topk uses its workspace for long rows; kvp_dims,
+ * kvp_workspace_bytes and kvp_score_tokens_static exist. */
 uint32_t kvp_version(void);
 
 #ifdef __cplusplus

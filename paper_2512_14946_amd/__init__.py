@@ -12,6 +12,6 @@ from .kvp import (  # noqa: F401
     KVP_EVAL_PV_MATRIX_CORES, KVP_OP_COMPRESS, KVP_OP_EVICT, KVP_OP_INSERT, kvp_policy_insert, kvp_utility_table,
     KVP_SCORE_KEYDIFF, KVP_SCORE_KNORM, kvp_score_keys, kvp_score_keys_workspace_bytes,
     kvp_score_workspace_bytes, kvp_select_topk, kvp_select_workspace_bytes, kvp_smooth_scores, kvp_strerror,
-    kvp_version,
+    kvp_version, kvp_workspace_bytes, KVP_WS_SCORE_TOKENS, KVP_WS_SCORE_KEYS, KVP_WS_SELECT_TOPK, KVP_WS_EVAL_CONFIGS,
     library_path,
 )

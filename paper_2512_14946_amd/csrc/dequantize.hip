@@ -217,5 +217,16 @@ extern "C" const char* kvp_strerror(int32_t code) {
   }
 }
 
-// major.minor.patch as 0x00MMmmpp; the minor number moves whenever a struct of the ABI gains a field
-extern "C" uint32_t kvp_version(void) { return 0x00010300u; }
+// major.minor.patch as 0x00MMmmpp; the minor number moves whenever the ABI gains a field or an entry point
+extern "C" uint32_t kvp_version(void) { return 0x00010400u; }
+
+extern "C" size_t kvp_workspace_bytes(int32_t op, const kvp_dims* d) {
+  if (!d) return 0;
+  switch (op) {
+    case KVP_WS_SCORE_TOKENS: return kvp_score_workspace_bytes(d->L, d->Hkv, d->Hq, d->W, d->T);
+    case KVP_WS_SCORE_KEYS: return kvp_score_keys_workspace_bytes(d->L, d->Hkv, d->T, d->method);
+    case KVP_WS_SELECT_TOPK: return kvp_select_workspace_bytes(d->n_rows, d->T, d->k);
+    case KVP_WS_EVAL_CONFIGS: return kvp_eval_workspace_bytes(d->L, d->Hkv, d->Hq, d->W, d->T, d->n_cfgs);
+    default: return 0;
+  }
+}

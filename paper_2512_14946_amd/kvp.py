@@ -47,6 +47,11 @@ class _PolicyOp(ctypes.Structure):
     _fields_ = [("ctx", _i32), ("cfg", _i32), ("tier", _i32), ("op", _i32)]
 
 
+class _Dims(ctypes.Structure):
+    _fields_ = [("L", _i64), ("Hkv", _i64), ("Hq", _i64), ("W", _i64), ("T", _i64), ("n_rows", _i64), ("k", _i64),
+                ("n_cfgs", _i32), ("method", _i32)]
+
+
 class _Config(ctypes.Structure):
     _fields_ = [("bits", _i32), ("group", _i32), ("keep_k", _i64)]
 
@@ -96,6 +101,8 @@ def _load(path: str = _LIB_PATH):
     lib.kvp_policy_insert.restype = _i32
     lib.kvp_policy_insert.argtypes = [_i32, _i32, _vp, _vp, _vp, P(_Tier), _i32, ctypes.c_double, _vp, _vp, _i32,
                                       P(_PolicyOp), _i32, P(_i32)]
+    lib.kvp_workspace_bytes.restype = _sz
+    lib.kvp_workspace_bytes.argtypes = [_i32, P(_Dims)]
     lib.kvp_keep_count.restype = _i64
     lib.kvp_keep_count.argtypes = [ctypes.c_double, _i64]
     lib.kvp_copy_bytes.restype = _i32
@@ -243,6 +250,16 @@ def kvp_strerror(code: int) -> str:
 
 def kvp_version() -> int:
     return int(_lib.kvp_version())
+
+
+KVP_WS_SCORE_TOKENS, KVP_WS_SCORE_KEYS, KVP_WS_SELECT_TOPK, KVP_WS_EVAL_CONFIGS = 0, 1, 2, 3
+
+
+def kvp_workspace_bytes(op: int, L: int = 0, Hkv: int = 0, Hq: int = 0, W: int = 0, T: int = 0, n_rows: int = 0,
+                        k: int = 0, n_cfgs: int = 0, method: int = 0) -> int:
+    """Scratch bytes of one call of entry point `op` (KVP_WS_*) for these sizes."""
+    d = _Dims(L, Hkv, Hq, W, T, n_rows, k, n_cfgs, method)
+    return int(_lib.kvp_workspace_bytes(int(op), ctypes.byref(d)))
 
 
 def kvp_keep_count(ratio: float, T: int) -> int:

@@ -109,6 +109,38 @@ def test_static_scratch_entry_point_rejects_oversized_shapes_on_the_host(lib):
     assert lib.kvp_score_workspace_bytes(1, 8, 64, 64, 131072) <= (4 << 20)
 
 
+def test_one_sizing_call_agrees_with_the_per_operation_helpers(lib):
+    class Dims(ctypes.Structure):
+        _fields_ = [(n, ctypes.c_int64) for n in ("L", "Hkv", "Hq", "W", "T", "n_rows", "k")] + \
+                   [("n_cfgs", ctypes.c_int32), ("method", ctypes.c_int32)]
+    lib.kvp_workspace_bytes.restype = ctypes.c_size_t
+    lib.kvp_workspace_bytes.argtypes = [ctypes.c_int32, ctypes.POINTER(Dims)]
+    for f, n in (("kvp_score_workspace_bytes", 5), ("kvp_select_workspace_bytes", 3)):
+        getattr(lib, f).restype = ctypes.c_size_t
+        getattr(lib, f).argtypes = [ctypes.c_int64] * n
+    lib.kvp_score_keys_workspace_bytes.restype = ctypes.c_size_t
+    lib.kvp_score_keys_workspace_bytes.argtypes = [ctypes.c_int64] * 3 + [ctypes.c_int32]
+    lib.kvp_eval_workspace_bytes.restype = ctypes.c_size_t
+    lib.kvp_eval_workspace_bytes.argtypes = [ctypes.c_int64] * 5 + [ctypes.c_int32]
+    d = Dims(32, 8, 32, 32, 8192, 112, 13108, 40, 1)
+    assert lib.kvp_workspace_bytes(0, ctypes.byref(d)) == lib.kvp_score_workspace_bytes(32, 8, 32, 32, 8192) > 0
+    assert lib.kvp_workspace_bytes(1, ctypes.byref(d)) == lib.kvp_score_keys_workspace_bytes(32, 8, 8192, 1) > 0
+    assert lib.kvp_workspace_bytes(3, ctypes.byref(d)) == lib.kvp_eval_workspace_bytes(32, 8, 32, 32, 8192, 40) > 0
+    assert lib.kvp_workspace_bytes(2, ctypes.byref(d)) == lib.kvp_select_workspace_bytes(112, 8192, 13108) == 0
+    d.T = 131072
+    long_rows = lib.kvp_select_workspace_bytes(112, 131072, 13108)
+    assert lib.kvp_workspace_bytes(2, ctypes.byref(d)) == long_rows
+    assert 112 * 16384 * 4 < long_rows < 112 * 16384 * 4 + (1 << 16)      # 64 KiB of candidate slots per row + counts
+    assert lib.kvp_select_workspace_bytes(112, (1 << 18) + 1, 5) == 0          # beyond the split path: one block per row
+    assert lib.kvp_workspace_bytes(9, ctypes.byref(d)) == 0 and lib.kvp_workspace_bytes(0, None) == 0
+    # a long row without its workspace is refused on the host
+    lib.kvp_select_topk.restype = ctypes.c_int32
+    lib.kvp_select_topk.argtypes = [ctypes.c_void_p] + [ctypes.c_int64] * 4 + [ctypes.c_void_p] * 2 + \
+        [ctypes.c_size_t, ctypes.c_void_p]
+    assert lib.kvp_select_topk(4096, 2, 40000, 40000, 100, 8192, None, 0, None) == -5
+    assert lib.kvp_select_topk(4096, 2, 40000, 40000, 100, 8192, 1 << 20, 64, None) == -5
+
+
 def test_binding_refuses_cpu_tensors():
     import torch
     import paper_2512_14946_amd as kvp
