@@ -8,12 +8,11 @@
 // library, and neither includes the other.
 //
 // The paper names the operations but gives no formula for the quantization
-// category (Background, "KV cache compression": quantization "reduces the
-// bit-width representation of KV entries"; Related work: uniform quantization)
-// and one sentence for the attention-score token dropping (Evaluation,
-// Baselines: snapkv "computes the cross attention between tokens near the
-// query and the earlier contexts, and drops those tokens with low
-// cross-attention scores").  The concrete arithmetic below is therefore a
+// category (Background, KV cache compression: entries stored at a lower bit
+// width; Related work: uniform quantization) and one sentence for the
+// attention-score token dropping (Evaluation, Baselines, snapkv: the earlier
+// context is scored by the attention it gets from the tokens next to the query,
+// and the lowest-scored tokens go).  The concrete arithmetic below is therefore a
 // stated reading (symmetric abs-max scaling, IEEE binary32 division,
 // round-half-to-even, lowest-index tie-break, keep count ceil(ratio*T)); each
 // reading is stated again at the function it governs.
@@ -714,10 +713,9 @@ int oracle_eval_configs(const uint16_t* q, int64_t W, int64_t Hq, int64_t q_sl, 
 }
 
 // Key-only token importance of the paper's two other token-dropping methods (Evaluation, Baselines):
-//   method 0, knorm:   "computes the L2 norm of the key cache, and drops those with low L2 norm"
+//   method 0, knorm:   tokens whose key has a small L2 norm are dropped
 //                      score[t] = ||k_t||_2                              (keep the largest)
-//   method 1, keydiff: "computes the average cosine similarity of every token to all other tokens,
-//                      and drops the tokens whose similarities are high"
+//   method 1, keydiff: tokens whose key is, on average, most similar (cosine) to all other keys are dropped
 //                      score[t] = - mean over t' != t of cos(k_t, k_t')  (keep the largest)
 // written out as the plain definitions (keydiff is the O(T^2 D) double loop).  A zero key has cosine
 // 0 with everything; T == 1 gives score 0.  With `tokens` (n of them) only those tokens are scored

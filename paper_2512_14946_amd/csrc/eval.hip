@@ -1,5 +1,5 @@
 // kvp_eval_configs: quality-loss proxy of every candidate (bits, group, keep_k) configuration of one
-// context (the paper's profiler compresses a KV cache "with different methods and ratios" and
+// context (the paper's profiler compresses a KV cache with every method and ratio of its pool and
 // scores every version; this is the quality term of its utility function with the attention-output
 // error standing in for the answer-similarity metric that needs model weights).
 //
