@@ -169,8 +169,18 @@ def alloc_paged(L: int, T: int, H: int, D: int, block_table: torch.Tensor, num_b
 
 # ------------------------------------------------------------------ marshalling
 
-def _stream(stream) -> int:
+# Marshalled structs are cached: a tensor keeps the struct built from it (keyed by its data pointer and element
+# count), a QPlane / PagedKV keeps its struct as long as it refers to the same tensor objects and sizes.  A call on
+# operands seen before then costs a few attribute reads instead of a dozen shape / stride / dtype queries, which is
+# most of the host time of a small, launch-bound call.
+
+_raw_stream = getattr(torch._C, "_cuda_getCurrentRawStream", None)
+
+
+def _stream(stream, like: torch.Tensor | None = None) -> int:
     if stream is None:
+        if _raw_stream is not None and like is not None:
+            return _raw_stream(like.get_device())
         return torch.cuda.current_stream().cuda_stream
     if isinstance(stream, torch.cuda.Stream):
         return stream.cuda_stream
@@ -184,15 +194,26 @@ def _need_cuda(*ts):
 
 
 def _view(t: torch.Tensor) -> _View:
+    c = getattr(t, "_kvp_view", None)
+    if c is not None and c[0] == t.data_ptr() and c[1] == t.numel():
+        return c[2]
     if t.dtype != torch.bfloat16 or t.dim() != 4:
         raise ValueError("expected a bf16 tensor [L][T][H][D]")
     if t.stride(3) != 1:
         raise ValueError("innermost dimension must be contiguous")
     L, T, H, D = t.shape
-    return _View(t.data_ptr(), L, T, H, D, t.stride(0), t.stride(1), t.stride(2))
+    v = _View(t.data_ptr(), L, T, H, D, t.stride(0), t.stride(1), t.stride(2))
+    try:
+        t._kvp_view = (t.data_ptr(), t.numel(), v)
+    except Exception:   # a tensor type that takes no attributes
+        pass
+    return v
 
 
 def _paged(p: PagedKV) -> _Paged:
+    c = p.__dict__.get("_c")
+    if c is not None and c[0] is p.pool and c[1] is p.block_table and c[2] == p.T and c[3] == p.pool.data_ptr():
+        return c[4]
     pool = p.pool
     if pool.dtype != torch.bfloat16 or pool.dim() != 5 or not pool[0].is_contiguous():
         raise ValueError("pool must be bf16 [L][num_blocks][bs][H][D], contiguous per layer")
@@ -201,10 +222,17 @@ def _paged(p: PagedKV) -> _Paged:
     L, NB, bs, H, D = pool.shape
     if p.block_table.numel() < (p.T + bs - 1) // bs:
         raise ValueError("block_table is shorter than ceil(T / bs)")
-    return _Paged(pool.data_ptr(), p.block_table.data_ptr(), L, NB, bs, H, D, p.T, pool.stride(0))
+    _need_cuda(pool, p.block_table)
+    v = _Paged(pool.data_ptr(), p.block_table.data_ptr(), L, NB, bs, H, D, p.T, pool.stride(0))
+    p.__dict__["_c"] = (p.pool, p.block_table, p.T, pool.data_ptr(), v)
+    return v
 
 
 def _qplane(q: QPlane) -> _QPlane:
+    c = q.__dict__.get("_c")
+    if (c is not None and c[0] is q.codes and c[1] is q.scales and c[2] is q.mins and c[3] == q.T and c[4] == q.bits
+            and c[5] == q.group and c[6] == q.group_axis and c[7] == q.codes.data_ptr()):
+        return c[8]
     if q.codes.dtype != torch.uint8 or q.scales.dtype != torch.float32:
         raise ValueError("codes must be uint8 and scales float32")
     if not (q.codes.is_contiguous() and q.scales.is_contiguous()):
@@ -219,7 +247,10 @@ def _qplane(q: QPlane) -> _QPlane:
         if q.mins.dtype != torch.float32 or not q.mins.is_contiguous() or tuple(q.mins.shape) != tuple(q.scales.shape):
             raise ValueError("mins must be contiguous float32 with the shape of scales")
         mins = q.mins.data_ptr()
-    return _QPlane(q.codes.data_ptr(), q.scales.data_ptr(), mins, q.bits, q.group, L, q.T, Tp, H, D, q.group_axis)
+    _need_cuda(q.codes, q.scales, q.mins)
+    v = _QPlane(q.codes.data_ptr(), q.scales.data_ptr(), mins, q.bits, q.group, L, q.T, Tp, H, D, q.group_axis)
+    q.__dict__["_c"] = (q.codes, q.scales, q.mins, q.T, q.bits, q.group, q.group_axis, q.codes.data_ptr(), v)
+    return v
 
 
 def _check(rc: int, what: str):
@@ -269,34 +300,37 @@ def kvp_keep_count(ratio: float, T: int) -> int:
 def kvp_quantize(src, dst: QPlane, keep_idx: torch.Tensor | None = None, stream=None) -> QPlane:
     """src: bf16 tensor [L][T][H][D] (strided view allowed) or PagedKV.  Fills dst.codes / dst.scales."""
     k = 0
+    kp = None
     if keep_idx is not None:
-        if keep_idx.dtype != torch.int32 or not keep_idx.is_contiguous() or keep_idx.dim() != 3:
-            raise ValueError("keep_idx must be contiguous int32 [L][H][k]")
+        if keep_idx.dtype != torch.int32 or not keep_idx.is_contiguous() or keep_idx.dim() != 3 or not keep_idx.is_cuda:
+            raise ValueError("keep_idx must be a contiguous int32 cuda tensor [L][H][k]")
         k = keep_idx.shape[2]
-    kp = keep_idx.data_ptr() if keep_idx is not None else None
+        kp = keep_idx.data_ptr()
     qp = _qplane(dst)
     if isinstance(src, PagedKV):
-        _need_cuda(src.pool, src.block_table, dst.codes, dst.scales, dst.mins, keep_idx)
         pg = _paged(src)
-        rc = _lib.kvp_quantize(None, ctypes.byref(pg), kp, k, ctypes.byref(qp), _stream(stream))
+        rc = _lib.kvp_quantize(None, ctypes.byref(pg), kp, k, ctypes.byref(qp), _stream(stream, dst.codes))
     else:
-        _need_cuda(src, dst.codes, dst.scales, dst.mins, keep_idx)
+        if not src.is_cuda:
+            raise ValueError("kvp_* operations run on the GPU only: tensors must live on a cuda device")
         vw = _view(src)
-        rc = _lib.kvp_quantize(ctypes.byref(vw), None, kp, k, ctypes.byref(qp), _stream(stream))
-    _check(rc, "kvp_quantize")
+        rc = _lib.kvp_quantize(ctypes.byref(vw), None, kp, k, ctypes.byref(qp), _stream(stream, dst.codes))
+    if rc != 0:
+        raise KVPError(rc, "kvp_quantize")
     return dst
 
 
 def kvp_dequantize_paged(src: QPlane, dst: PagedKV, stream=None) -> PagedKV:
-    _need_cuda(src.codes, src.scales, src.mins, dst.pool, dst.block_table)
     qp, pg = _qplane(src), _paged(dst)
-    _check(_lib.kvp_dequantize_paged(ctypes.byref(qp), ctypes.byref(pg), _stream(stream)), "kvp_dequantize_paged")
+    rc = _lib.kvp_dequantize_paged(ctypes.byref(qp), ctypes.byref(pg), _stream(stream, src.codes))
+    if rc != 0:
+        raise KVPError(rc, "kvp_dequantize_paged")
     return dst
 
 
 def kvp_dequantize_paged_scatter(src: QPlane, keep_idx: torch.Tensor, dst: PagedKV, stream=None) -> PagedKV:
     """Restore the k slots of a dropped+quantized plane at tokens keep_idx int32 [L][H][k] of a T-token pool."""
-    _need_cuda(src.codes, src.scales, src.mins, keep_idx, dst.pool, dst.block_table)
+    _need_cuda(keep_idx)
     qp, pg = _qplane(src), _paged(dst)
     if keep_idx.dtype != torch.int32 or not keep_idx.is_contiguous() or tuple(keep_idx.shape) != (qp.L, qp.H, src.T):
         raise ValueError("keep_idx must be contiguous int32 [L][H][k] with k = src.T")
