@@ -228,13 +228,19 @@ int32_t kvp_eval_configs(const kvp_view* q_win, const kvp_view* k, const kvp_vie
                          int32_t n_cfgs, float* loss, float* partial, void* ws, size_t ws_bytes, void* stream);
 size_t kvp_eval_workspace_bytes(int64_t L, int64_t Hkv, int64_t Hq, int64_t W, int64_t T, int32_t n_cfgs);
 
-/* The same computation with implementation flags (0 = kvp_eval_configs).
- * KVP_EVAL_PV_MATRIX_CORES: form the P.V product of the proxy on the matrix cores (P as the sum of
- * two bf16 terms, relative error 2^-18, fp32 accumulation) instead of fp32 on the vector ALU; about
- * 2.5x faster, results agree with the default within 1e-5 relative.  Off by default: the scope of
- * this library reserves the matrix cores for the query-window x key contraction.  Unknown flag
- * bits: KVP_ERR_UNSUPPORTED. */
-enum { KVP_EVAL_PV_MATRIX_CORES = 1 };
+/* The same computation with implementation flags (0 = kvp_eval_configs).  The flags choose how the P.V
+ * product of the proxy is formed; logits, softmax statistics and accumulation are fp32 in every mode.
+ * 0 (default): vector ALU with 16-bit operands: the probabilities rounded to fp16 (nearest even; the row sums
+ *   use the rounded values) and V-hat as fp16, two tokens per v_dot2_f32_f16.  V-hat is a bf16 value and exact in
+ *   fp16 for 2^-14 <= |v| <= 65504; smaller magnitudes round to multiples of 2^-24 and larger ones saturate at 65504,
+ *   so caches with |V| beyond that range need one of the other modes.  Losses agree with KVP_EVAL_PV_FP32 within
+ *   1e-4 relative (3e-5 measured on the 40-configuration sweep).
+ * KVP_EVAL_PV_FP32: vector ALU with fp32 probabilities and V-hat, one fma per token and output; 1.2x slower.
+ * KVP_EVAL_PV_MATRIX_CORES: on the matrix cores (P as the sum of two bf16 terms, relative error 2^-18); the
+ *   fastest; agrees with KVP_EVAL_PV_FP32 within 1e-5 relative.  Not the default because the scope of this
+ *   library reserves the matrix cores for the query-window x key contraction.
+ * The two flags exclude each other; both set, or unknown flag bits: KVP_ERR_UNSUPPORTED. */
+enum { KVP_EVAL_PV_MATRIX_CORES = 1, KVP_EVAL_PV_FP32 = 2 };
 int32_t kvp_eval_configs_ex(const kvp_view* q_win, const kvp_view* k, const kvp_view* v, const kvp_config* cfgs,
                             int32_t n_cfgs, float* loss, float* partial, void* ws, size_t ws_bytes, uint32_t flags,
                             void* stream);

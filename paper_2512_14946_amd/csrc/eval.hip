@@ -26,8 +26,12 @@
 // registers) and computes S^T = K-hat Q^T with 8 v_mfma_f32_32x32x16_bf16, so a lane holds one
 // query and 16 keys and the online-softmax statistics stay lane-private.  The P.V product has two
 // implementations, chosen per call:
-//   vector ALU (default): the probabilities go to LDS in fp32 and each thread accumulates an 8x8
-//     tile of the 128x128 output in fp32 (the matrix cores are kept for the query x key contraction);
+//   vector ALU, 16-bit operands (default): token pairs of the probabilities (rounded to fp16, nearest even) and
+//     of V-hat (a bf16 value, exact in fp16 for 2^-14 <= |v| <= 65504) go to LDS as packed halves, and each thread
+//     accumulates an 8x8 tile of the 128x128 output in fp32 with v_dot2_f32_f16, two tokens per instruction (the
+//     matrix cores are kept for the query x key contraction).  The row sums use the rounded probabilities, so every
+//     output stays a convex combination of V-hat rows; rounding P moves the losses by less than 1e-4 relative;
+//   vector ALU, fp32 (KVP_EVAL_PV_FP32): probabilities and V-hat in LDS as fp32, one fma per token and output;
 //   matrix cores (KVP_EVAL_PV_MATRIX_CORES): O^T = V-hat^T P^T with V-hat exact in bf16 (it is a
 //     dequantized value) and each probability split into two bf16 terms hi + lo (the loss is a
 //     difference of two nearly equal outputs: rounding P to one bf16 moves the losses by 1e-3
@@ -44,6 +48,10 @@ namespace {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(16))) float floatx16;
+typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+
+// implementations of the P.V product (template argument of attention_kernel)
+constexpr int kPvDot2 = 0, kPvMatrix = 1, kPvFp32 = 2;
 
 // resident waves per SIMD the attention kernel is compiled for (2 blocks per CU; 3 would spill)
 #ifndef KVP_EVAL_WAVES_PER_SIMD
@@ -91,6 +99,24 @@ __device__ __forceinline__ bf16x8 as_bf16x8(uint4 v) {
   union { uint4 u; bf16x8 b; } c;
   c.u = v;
   return c.b;
+}
+
+__device__ __forceinline__ uint32_t as_u32(half2_t h) {
+  union { half2_t h; uint32_t u; } c;
+  c.h = h;
+  return c.u;
+}
+__device__ __forceinline__ half2_t as_half2(uint32_t u) {
+  union { uint32_t u; half2_t h; } c;
+  c.u = u;
+  return c.h;
+}
+// two floats that are exact in fp16 (or beyond its range: rounded toward zero, clamped at 65504) as packed halves
+__device__ __forceinline__ uint32_t pack_f16x2(float lo, float hi) {
+  typedef __fp16 fp16x2 __attribute__((ext_vector_type(2)));
+  union { fp16x2 h; uint32_t u; } c;
+  c.h = __builtin_amdgcn_cvt_pkrtz(lo, hi);
+  return c.u;
 }
 
 __device__ __forceinline__ int acc_row(int lane, int v) { return (lane >> 5) * 4 + (v >> 2) * 8 + (v & 3); }
@@ -247,14 +273,21 @@ __device__ __forceinline__ WorkItem work_item(const EvalArgs& a) {
 
 // One launch covers every stream; the 16-bit stream also walks the tokens no keep level holds and so ends
 // as the reference O_full.  Outputs are compared afterwards (compare_kernel).
-// PV_MFMA: the P.V product on the matrix cores (two-term bf16 split of P) instead of the vector ALU.
-template <bool PV_MFMA>
+// PV: how the P.V product is formed (kPvDot2: packed fp16 pairs on the vector ALU; kPvMatrix: two-term bf16 split
+// of P on the matrix cores; kPvFp32: fp32 on the vector ALU).
+template <int PV>
 __global__ __launch_bounds__(kThreads, KVP_EVAL_WAVES_PER_SIMD) void attention_kernel(const EvalArgs a) {
   __shared__ __attribute__((aligned(16))) uint16_t k_s[kTile * kPitch];
   // V-hat: transposed bf16 for the matrix cores (see v_operand), or fp32 [token][channel] for the vector ALU
+  constexpr bool PV_MFMA = PV == kPvMatrix;
+  constexpr bool PV_FP32 = PV == kPvFp32;
+  constexpr bool PV_DOT2 = PV == kPvDot2;
   __shared__ __attribute__((aligned(16))) uint16_t vt_s[PV_MFMA ? kVtRows * kVtPitch : 8];
-  __shared__ __attribute__((aligned(16))) float v_s[PV_MFMA ? 4 : kTile * kHeadDim];
-  __shared__ __attribute__((aligned(16))) float p_s[PV_MFMA ? 4 : kTile * kRowsPerBlock];
+  __shared__ __attribute__((aligned(16))) float v_s[PV_FP32 ? kTile * kHeadDim : 4];
+  __shared__ __attribute__((aligned(16))) float p_s[PV_FP32 ? kTile * kRowsPerBlock : 4];
+  // token pairs as packed halves: [pair][channel] and [pair][query row]; low half = the even token
+  __shared__ __attribute__((aligned(16))) uint32_t v2_s[PV_DOT2 ? (kTile / 2) * kHeadDim : 4];
+  __shared__ __attribute__((aligned(16))) uint32_t p2_s[PV_DOT2 ? (kTile / 2) * kRowsPerBlock : 4];
   __shared__ __attribute__((aligned(16))) float alpha_s[PV_MFMA ? 4 : kRowsPerBlock];
   __shared__ __attribute__((aligned(16))) float z_s[PV_MFMA ? 4 : kRowsPerBlock];
   __shared__ int tok_s[kTile];
@@ -337,6 +370,17 @@ __global__ __launch_bounds__(kThreads, KVP_EVAL_WAVES_PER_SIMD) void attention_k
     *reinterpret_cast<uint4*>(k_s + tk * kPitch + part * 8) = kp;
     if constexpr (PV_MFMA) {
       stage_v_transposed(vt_s, vp, tk >> 2, part, lane);
+    } else if constexpr (PV_DOT2) {
+      // Tokens tk and tk ^ 1 sit 16 lanes apart.  The even one keeps channels 0..3 of its 8, the odd one channels
+      // 4..7; each sends the other half across and packs (even token, odd token) per channel.
+      const bool odd = (tk & 1) != 0;
+      const uint32_t got0 = __shfl_xor(odd ? vp.x : vp.z, 16, 64), got1 = __shfl_xor(odd ? vp.y : vp.w, 16, 64);
+      const uint32_t own0 = odd ? vp.z : vp.x, own1 = odd ? vp.w : vp.y;
+      const uint32_t e0 = odd ? got0 : own0, e1 = odd ? got1 : own1;   // the even token's four channels (bf16 pairs)
+      const uint32_t o0 = odd ? own0 : got0, o1 = odd ? own1 : got1;   // the odd token's
+      const uint4 packed = make_uint4(pack_f16x2(bf16lo(e0), bf16lo(o0)), pack_f16x2(bf16hi(e0), bf16hi(o0)),
+                                      pack_f16x2(bf16lo(e1), bf16lo(o1)), pack_f16x2(bf16hi(e1), bf16hi(o1)));
+      *reinterpret_cast<uint4*>(v2_s + (tk >> 1) * kHeadDim + part * 8 + (odd ? 4 : 0)) = packed;
     } else {
       float* vrow = v_s + tk * kHeadDim + part * 8;
       *reinterpret_cast<float4*>(vrow) = make_float4(bf16lo(vp.x), bf16hi(vp.x), bf16lo(vp.y), bf16hi(vp.y));
@@ -439,19 +483,31 @@ __global__ __launch_bounds__(kThreads, KVP_EVAL_WAVES_PER_SIMD) void attention_k
             }
         }
       } else {
-        // probabilities to LDS in fp32, [token][query row]
         float zsum = 0.0f;
         const int rloc = wave * 32 + (lane & 31);
+        if constexpr (PV_DOT2) {
+          // probabilities to LDS as fp16 pairs of adjacent tokens, [pair][query row]; the row sum takes the rounded values
 #pragma unroll
-        for (int vv = 0; vv < 16; ++vv) {
-          const float p = __builtin_amdgcn_exp2f(fmaf(acc[vv], a.scale2, -m_safe));
-          zsum += p;
-          p_s[acc_row(lane, vv) * kRowsPerBlock + rloc] = p;
+          for (int e = 0; e < 8; ++e) {
+            const float p0 = __builtin_amdgcn_exp2f(fmaf(acc[2 * e], a.scale2, -m_safe));
+            const float p1 = __builtin_amdgcn_exp2f(fmaf(acc[2 * e + 1], a.scale2, -m_safe));
+            const half2_t ph = {static_cast<_Float16>(p0), static_cast<_Float16>(p1)};
+            zsum += static_cast<float>(ph[0]) + static_cast<float>(ph[1]);
+            p2_s[(acc_row(lane, 2 * e) >> 1) * kRowsPerBlock + rloc] = as_u32(ph);
+          }
+        } else {
+          // probabilities to LDS in fp32, [token][query row]
+#pragma unroll
+          for (int vv = 0; vv < 16; ++vv) {
+            const float p = __builtin_amdgcn_exp2f(fmaf(acc[vv], a.scale2, -m_safe));
+            zsum += p;
+            p_s[acc_row(lane, vv) * kRowsPerBlock + rloc] = p;
+          }
         }
         run_z = run_z * alpha + zsum;
         if (lane < 32) alpha_s[rloc] = alpha;
         __syncthreads();
-        // ---- O = O * alpha + P V-hat on the vector ALU, fp32 ----
+        // ---- O = O * alpha + P V-hat on the vector ALU, fp32 accumulation ----
         const float4 a0 = *reinterpret_cast<const float4*>(alpha_s + 4 * ty);
         const float4 a1 = *reinterpret_cast<const float4*>(alpha_s + 64 + 4 * ty);
         const float al[8] = {a0.x, a0.y, a0.z, a0.w, a1.x, a1.y, a1.z, a1.w};
@@ -459,18 +515,35 @@ __global__ __launch_bounds__(kThreads, KVP_EVAL_WAVES_PER_SIMD) void attention_k
         for (int i = 0; i < 8; ++i)
 #pragma unroll
           for (int j = 0; j < 8; ++j) o[8 * i + j] *= al[i];
+        if constexpr (PV_DOT2) {
 #pragma unroll 4
-        for (int tk = 0; tk < kTile; ++tk) {
-          const float4 p0 = *reinterpret_cast<const float4*>(p_s + tk * kRowsPerBlock + 4 * ty);
-          const float4 p1 = *reinterpret_cast<const float4*>(p_s + tk * kRowsPerBlock + 64 + 4 * ty);
-          const float4 v0 = *reinterpret_cast<const float4*>(v_s + tk * kHeadDim + 4 * tx);
-          const float4 v1 = *reinterpret_cast<const float4*>(v_s + tk * kHeadDim + 64 + 4 * tx);
-          const float pr[8] = {p0.x, p0.y, p0.z, p0.w, p1.x, p1.y, p1.z, p1.w};
-          const float vc[8] = {v0.x, v0.y, v0.z, v0.w, v1.x, v1.y, v1.z, v1.w};
+          for (int tp = 0; tp < kTile / 2; ++tp) {
+            const uint4 p0 = *reinterpret_cast<const uint4*>(p2_s + tp * kRowsPerBlock + 4 * ty);
+            const uint4 p1 = *reinterpret_cast<const uint4*>(p2_s + tp * kRowsPerBlock + 64 + 4 * ty);
+            const uint4 v0 = *reinterpret_cast<const uint4*>(v2_s + tp * kHeadDim + 4 * tx);
+            const uint4 v1 = *reinterpret_cast<const uint4*>(v2_s + tp * kHeadDim + 64 + 4 * tx);
+            const uint32_t pr[8] = {p0.x, p0.y, p0.z, p0.w, p1.x, p1.y, p1.z, p1.w};
+            const uint32_t vc[8] = {v0.x, v0.y, v0.z, v0.w, v1.x, v1.y, v1.z, v1.w};
 #pragma unroll
-          for (int i = 0; i < 8; ++i)
+            for (int i = 0; i < 8; ++i)
 #pragma unroll
-            for (int j = 0; j < 8; ++j) o[8 * i + j] = fmaf(pr[i], vc[j], o[8 * i + j]);
+              for (int j = 0; j < 8; ++j)
+                o[8 * i + j] = __builtin_amdgcn_fdot2(as_half2(pr[i]), as_half2(vc[j]), o[8 * i + j], false);
+          }
+        } else {
+#pragma unroll 4
+          for (int tk = 0; tk < kTile; ++tk) {
+            const float4 p0 = *reinterpret_cast<const float4*>(p_s + tk * kRowsPerBlock + 4 * ty);
+            const float4 p1 = *reinterpret_cast<const float4*>(p_s + tk * kRowsPerBlock + 64 + 4 * ty);
+            const float4 v0 = *reinterpret_cast<const float4*>(v_s + tk * kHeadDim + 4 * tx);
+            const float4 v1 = *reinterpret_cast<const float4*>(v_s + tk * kHeadDim + 64 + 4 * tx);
+            const float pr[8] = {p0.x, p0.y, p0.z, p0.w, p1.x, p1.y, p1.z, p1.w};
+            const float vc[8] = {v0.x, v0.y, v0.z, v0.w, v1.x, v1.y, v1.z, v1.w};
+#pragma unroll
+            for (int i = 0; i < 8; ++i)
+#pragma unroll
+              for (int j = 0; j < 8; ++j) o[8 * i + j] = fmaf(pr[i], vc[j], o[8 * i + j]);
+          }
         }
       }
     }
@@ -633,7 +706,8 @@ extern "C" int32_t kvp_eval_configs_ex(const kvp_view* q_win, const kvp_view* k,
                                        const kvp_config* cfgs, int32_t n_cfgs, float* loss, float* partial, void* ws,
                                        size_t ws_bytes, uint32_t flags, void* stream) {
   using namespace kvp;
-  if (flags & ~static_cast<uint32_t>(KVP_EVAL_PV_MATRIX_CORES)) return KVP_ERR_UNSUPPORTED;
+  if (flags & ~static_cast<uint32_t>(KVP_EVAL_PV_MATRIX_CORES | KVP_EVAL_PV_FP32)) return KVP_ERR_UNSUPPORTED;
+  if ((flags & KVP_EVAL_PV_MATRIX_CORES) && (flags & KVP_EVAL_PV_FP32)) return KVP_ERR_UNSUPPORTED;
   int32_t rc = check_view(q_win);
   if (rc != KVP_OK) return rc;
   rc = check_view(k);
@@ -746,10 +820,13 @@ extern "C" int32_t kvp_eval_configs_ex(const kvp_view* q_win, const kvp_view* k,
   build_order_kernel<<<dim3(static_cast<unsigned>(p.LH)), kOrderThreads, 0, st>>>(a);
   const dim3 grid(static_cast<unsigned>(kXcds * ceil_div(items, kXcds)));
   if (flags & KVP_EVAL_PV_MATRIX_CORES) {
-    attention_kernel<true><<<grid, kThreads, 0, st>>>(a);
+    attention_kernel<kPvMatrix><<<grid, kThreads, 0, st>>>(a);
     compare_kernel<true><<<grid, kThreads, 0, st>>>(a);
+  } else if (flags & KVP_EVAL_PV_FP32) {
+    attention_kernel<kPvFp32><<<grid, kThreads, 0, st>>>(a);
+    compare_kernel<false><<<grid, kThreads, 0, st>>>(a);
   } else {
-    attention_kernel<false><<<grid, kThreads, 0, st>>>(a);
+    attention_kernel<kPvDot2><<<grid, kThreads, 0, st>>>(a);
     compare_kernel<false><<<grid, kThreads, 0, st>>>(a);
   }
   finish_kernel<<<1, kFinishThreads, 0, st>>>(a);

@@ -446,9 +446,9 @@ def kvp_eval_workspace_bytes(L: int, Hkv: int, Hq: int, W: int, T: int, n_cfgs: 
 def kvp_eval_configs(q_win: torch.Tensor, k: torch.Tensor, v: torch.Tensor, cfgs: Iterable[Sequence[int]],
                      loss: torch.Tensor | None = None, partial: torch.Tensor | None = None,
                      ws: torch.Tensor | None = None, stream=None, want_partial: bool = False,
-                     pv_matrix_cores: bool = False):
+                     pv_matrix_cores: bool = False, pv_fp32: bool = False):
     """cfgs: (bits, group, keep_k) triples.  Returns loss f32 [n] (and partial f32 [L][n][2] if asked).
-    pv_matrix_cores selects kvp_eval_configs_ex with KVP_EVAL_PV_MATRIX_CORES."""
+    pv_matrix_cores / pv_fp32 select kvp_eval_configs_ex with KVP_EVAL_PV_MATRIX_CORES / KVP_EVAL_PV_FP32."""
     _need_cuda(q_win, k, v, loss, partial, ws)
     cfgs = list(cfgs)
     n = len(cfgs)
@@ -462,9 +462,10 @@ def kvp_eval_configs(q_win: torch.Tensor, k: torch.Tensor, v: torch.Tensor, cfgs
     ws, wp, wb = _workspace(ws, kvp_eval_workspace_bytes(L, Hkv, Hq, W, T, n), k.device, stream)
     qv, kv, vv = _view(q_win), _view(k), _view(v)
     pp = partial.data_ptr() if partial is not None else None
-    if pv_matrix_cores:
+    flags = (KVP_EVAL_PV_MATRIX_CORES if pv_matrix_cores else 0) | (KVP_EVAL_PV_FP32 if pv_fp32 else 0)
+    if flags:
         _check(_lib.kvp_eval_configs_ex(ctypes.byref(qv), ctypes.byref(kv), ctypes.byref(vv), arr, n, loss.data_ptr(),
-                                        pp, wp, wb, KVP_EVAL_PV_MATRIX_CORES, _stream(stream)), "kvp_eval_configs_ex")
+                                        pp, wp, wb, flags, _stream(stream)), "kvp_eval_configs_ex")
     else:
         _check(_lib.kvp_eval_configs(ctypes.byref(qv), ctypes.byref(kv), ctypes.byref(vv), arr, n, loss.data_ptr(),
                                      pp, wp, wb, _stream(stream)), "kvp_eval_configs")
@@ -473,6 +474,7 @@ def kvp_eval_configs(q_win: torch.Tensor, k: torch.Tensor, v: torch.Tensor, cfgs
 
 KVP_OP_INSERT, KVP_OP_COMPRESS, KVP_OP_EVICT = 0, 1, 2
 KVP_EVAL_PV_MATRIX_CORES = 1
+KVP_EVAL_PV_FP32 = 2
 
 
 def _tiers(tiers):

@@ -82,7 +82,8 @@ def test_validation_rejects_before_any_launch(lib):
     lib.kvp_eval_configs_ex.restype = ctypes.c_int32
     lib.kvp_eval_configs_ex.argtypes = [ctypes.c_void_p] * 4 + [ctypes.c_int32] + [ctypes.c_void_p] * 3 + \
         [ctypes.c_size_t, ctypes.c_uint32, ctypes.c_void_p]
-    assert lib.kvp_eval_configs_ex(None, None, None, None, 1, None, None, None, 0, 2, None) == -4   # unknown flag
+    assert lib.kvp_eval_configs_ex(None, None, None, None, 1, None, None, None, 0, 4, None) == -4   # unknown flag
+    assert lib.kvp_eval_configs_ex(None, None, None, None, 1, None, None, None, 0, 3, None) == -4   # exclusive flags
     assert lib.kvp_eval_configs_ex(None, None, None, None, 1, None, None, None, 0, 1, None) == -1
     lib.kvp_score_keys.restype = ctypes.c_int32
     lib.kvp_score_keys.argtypes = [ctypes.c_void_p, ctypes.c_int32] + [ctypes.c_void_p] * 2 + [ctypes.c_size_t, ctypes.c_void_p]

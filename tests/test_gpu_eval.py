@@ -16,14 +16,17 @@ def _kvp():
     return kvp
 
 
-def _case(L, W, G, H, T, cfgs, seed, outlier=8.0, pv_matrix_cores=False):
+PV_MODES = {"pv_dot2_fp16": {}, "pv_fp32": {"pv_fp32": True}, "pv_matrix_cores": {"pv_matrix_cores": True}}
+
+
+def _case(L, W, G, H, T, cfgs, seed, outlier=8.0, pv="pv_dot2_fp16"):
     kvp = _kvp()
     D = 128
-    print("[case] eval", dict(L=L, W=W, G=G, H=H, T=T, n=len(cfgs), pv_matrix_cores=pv_matrix_cores), flush=True)
+    print("[case] eval", dict(L=L, W=W, G=G, H=H, T=T, n=len(cfgs), pv=pv), flush=True)
     K, V = workloads.make_kv(L, T, H, D, seed=seed, outlier_scale=outlier)
     Q = workloads.make_q(L, W, G * H, D, seed=seed)
     loss, partial = kvp.kvp_eval_configs(Q.to(DEV), K.to(DEV), V.to(DEV), cfgs, want_partial=True,
-                                         pv_matrix_cores=pv_matrix_cores)
+                                         **PV_MODES[pv])
     torch.cuda.synchronize()
     loss, partial = loss.cpu().numpy(), partial.cpu().numpy()
     ref, ref_partial = oracle.eval_configs(torch_bits(Q), torch_bits(K), torch_bits(V), cfgs)
@@ -40,15 +43,15 @@ def _sweep(T):
     return [(b, g, k) for (b, g) in variants for k in ks]
 
 
-BOTH_PV = pytest.mark.parametrize("pv_matrix_cores", [False, True], ids=["pv_vector_alu", "pv_matrix_cores"])
+BOTH_PV = pytest.mark.parametrize("pv", list(PV_MODES))
 
 
 @BOTH_PV
-def test_full_candidate_sweep_small(pv_matrix_cores):
+def test_full_candidate_sweep_small(pv):
     T = 300                                            # ragged: 300 = 9 tiles of 32 + 12
     cfgs = _sweep(T)
     assert len(cfgs) == 40
-    loss, ref = _case(2, 32, 4, 2, T, cfgs, seed=0, pv_matrix_cores=pv_matrix_cores)
+    loss, ref = _case(2, 32, 4, 2, T, cfgs, seed=0, pv=pv)
     assert loss[3] == 0.0                              # (16 bits, keep all) is the identity, exactly
     order = {c: i for i, c in enumerate(cfgs)}
     for g in (32, 64, 128):                            # fewer bits, larger loss
@@ -56,31 +59,47 @@ def test_full_candidate_sweep_small(pv_matrix_cores):
 
 
 @BOTH_PV
-def test_padded_row_blocks_and_tiny_keep(pv_matrix_cores):
+def test_padded_row_blocks_and_tiny_keep(pv):
     T = 200
     cfgs = [(16, 0, T), (8, 128, T), (4, 32, 77), (2, 64, 33), (16, 0, 5), (4, 64, 1)]
     # M = 224: two row blocks, the second partly filled
-    _case(1, 32, 7, 2, T, cfgs, seed=1, outlier=16.0, pv_matrix_cores=pv_matrix_cores)
+    _case(1, 32, 7, 2, T, cfgs, seed=1, outlier=16.0, pv=pv)
 
 
 @BOTH_PV
-def test_many_rows_and_duplicates(pv_matrix_cores):
+def test_many_rows_and_duplicates(pv):
     T = 130
     cfgs = [(8, 32, 64), (8, 32, 64), (16, 0, 64), (2, 32, T)]
-    loss, _ = _case(1, 64, 8, 1, T, cfgs, seed=2, pv_matrix_cores=pv_matrix_cores)      # M = 512: four row blocks
+    loss, _ = _case(1, 64, 8, 1, T, cfgs, seed=2, pv=pv)      # M = 512: four row blocks
     assert loss[0] == loss[1]
 
 
 @BOTH_PV
-def test_no_16_bit_config_and_no_keep_all(pv_matrix_cores):
+def test_no_16_bit_config_and_no_keep_all(pv):
     """No configuration asks for 16 bits and none keeps every token: the reference comes from a hidden stream that
     walks the tokens no keep level holds as well."""
     T = 150
     cfgs = [(4, 64, 50), (8, 128, 100), (2, 32, 100)]
-    _case(2, 32, 4, 2, T, cfgs, seed=3, pv_matrix_cores=pv_matrix_cores)
-    _case(1, 16, 2, 1, 97, [(8, 32, 40)], seed=4, pv_matrix_cores=pv_matrix_cores)      # a single configuration
+    _case(2, 32, 4, 2, T, cfgs, seed=3, pv=pv)
+    _case(1, 16, 2, 1, 97, [(8, 32, 40)], seed=4, pv=pv)      # a single configuration
     # the 16-bit codec is listed last and never with all tokens
-    _case(1, 32, 4, 1, T, [(2, 128, 75), (4, 32, 20), (16, 0, 75)], seed=5, pv_matrix_cores=pv_matrix_cores)
+    _case(1, 32, 4, 1, T, [(2, 128, 75), (4, 32, 20), (16, 0, 75)], seed=5, pv=pv)
+
+
+def test_pv_modes_agree():
+    """The three forms of the P.V product against each other on one input: the matrix-core form (two-term bf16
+    split of P) follows the fp32 form to 1e-4, the default form (P rounded to fp16) to 2e-3."""
+    kvp = _kvp()
+    L, W, G, H, T, D = 2, 32, 4, 2, 1000, 128
+    print("[case] eval modes", dict(L=L, W=W, G=G, H=H, T=T), flush=True)
+    K, V = workloads.make_kv(L, T, H, D, seed=9, outlier_scale=8.0)
+    Q = workloads.make_q(L, W, G * H, D, seed=9)
+    cfgs = _sweep(T)
+    out = {m: kvp.kvp_eval_configs(Q.to(DEV), K.to(DEV), V.to(DEV), cfgs, **kw).cpu().numpy() for m, kw in PV_MODES.items()}
+    ref = out["pv_fp32"]
+    assert np.all(np.abs(out["pv_matrix_cores"] - ref) <= 1e-4 * ref + 1e-7)
+    assert np.all(np.abs(out["pv_dot2_fp16"] - ref) <= 2e-3 * ref + 1e-6)
+    assert out["pv_dot2_fp16"][3] == 0.0 and ref[3] == 0.0
 
 
 def test_errors():
@@ -93,3 +112,5 @@ def test_errors():
         kvp.kvp_eval_configs(q, k, k, [(4, 32, 65)])
     with pytest.raises(kvp.KVPError):
         kvp.kvp_eval_configs(q, k, k, [(4, 32, 8)], ws=torch.empty(16, dtype=torch.uint8, device=DEV))
+    with pytest.raises(kvp.KVPError):                  # the two P.V flags exclude each other
+        kvp.kvp_eval_configs(q, k, k, [(4, 32, 8)], pv_matrix_cores=True, pv_fp32=True)

@@ -285,8 +285,11 @@ def test_long_context_score_full_shape_one_head():
         assert np.all(np.abs(got - ref) <= 1e-2 * np.abs(ref) + 1e-4 * G * W / T), (l, h)
 
 
-@pytest.mark.parametrize("pv_matrix_cores", [False, True], ids=["pv_vector_alu", "pv_matrix_cores"])
-def test_utility_sweep_context_properties_and_sampled_head(pv_matrix_cores):
+_PV = {"pv_dot2_fp16": {}, "pv_fp32": {"pv_fp32": True}, "pv_matrix_cores": {"pv_matrix_cores": True}}
+
+
+@pytest.mark.parametrize("pv", list(_PV))
+def test_utility_sweep_context_properties_and_sampled_head(pv):
     kvp = _kvp()
     c = workloads.CONFIGS["utility_sweep"]
     L, T, H, D, G, W = c["L"], c["T"], c["H"], c["D"], c["G"], c["W"]
@@ -297,7 +300,7 @@ def test_utility_sweep_context_properties_and_sampled_head(pv_matrix_cores):
     assert ks == [2048, 4096, 6144, 8192]
     variants = [(16, 0)] + [(b, g) for b in c["bits_set"] for g in c["group_set"]]
     cfgs = [(b, g, kk) for (b, g) in variants for kk in ks]
-    loss, partial = kvp.kvp_eval_configs(Q, K, V, cfgs, want_partial=True, pv_matrix_cores=pv_matrix_cores)
+    loss, partial = kvp.kvp_eval_configs(Q, K, V, cfgs, want_partial=True, **_PV[pv])
     torch.cuda.synchronize()
     loss = loss.cpu().numpy().reshape(len(variants), len(ks))
     assert loss[0, 3] == 0.0                                               # identity row
@@ -324,7 +327,7 @@ def test_utility_sweep_context_properties_and_sampled_head(pv_matrix_cores):
     sub = [(16, 0, T), (8, 128, T), (4, 64, 4096), (2, 32, 2048), (16, 0, 2048)]
     l, h = 7, 2
     Qs, Ks, Vs = Q[l:l + 1, :, h * G:(h + 1) * G], K[l:l + 1, :, h:h + 1], V[l:l + 1, :, h:h + 1]
-    got = kvp.kvp_eval_configs(Qs, Ks, Vs, sub, pv_matrix_cores=pv_matrix_cores)
+    got = kvp.kvp_eval_configs(Qs, Ks, Vs, sub, **_PV[pv])
     torch.cuda.synchronize()
     ref1, _ = oracle.eval_configs(torch_bits(Qs), torch_bits(Ks), torch_bits(Vs), sub)
     got = got.cpu().numpy()
