@@ -371,13 +371,14 @@ __global__ __launch_bounds__(kThreads, KVP_EVAL_WAVES_PER_SIMD) void attention_k
     if constexpr (PV_MFMA) {
       stage_v_transposed(vt_s, vp, tk >> 2, part, lane);
     } else if constexpr (PV_DOT2) {
-      // Tokens tk and tk ^ 1 sit 16 lanes apart.  The even one keeps channels 0..3 of its 8, the odd one channels
-      // 4..7; each sends the other half across and packs (even token, odd token) per channel.
+      // Tokens tk and tk ^ 1 sit 16 lanes apart (tk even: an even 16-lane row).  v_permlane16_swap exchanges the
+      // first operand's odd rows with the second operand's even rows: afterwards the even token's lane holds
+      // channels 0..3 of both tokens and the odd token's lane channels 4..7, even token first.
+      typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
       const bool odd = (tk & 1) != 0;
-      const uint32_t got0 = __shfl_xor(odd ? vp.x : vp.z, 16, 64), got1 = __shfl_xor(odd ? vp.y : vp.w, 16, 64);
-      const uint32_t own0 = odd ? vp.z : vp.x, own1 = odd ? vp.w : vp.y;
-      const uint32_t e0 = odd ? got0 : own0, e1 = odd ? got1 : own1;   // the even token's four channels (bf16 pairs)
-      const uint32_t o0 = odd ? own0 : got0, o1 = odd ? own1 : got1;   // the odd token's
+      const u32x2 c01 = __builtin_amdgcn_permlane16_swap(vp.x, vp.z, false, false);
+      const u32x2 c23 = __builtin_amdgcn_permlane16_swap(vp.y, vp.w, false, false);
+      const uint32_t e0 = c01[0], o0 = c01[1], e1 = c23[0], o1 = c23[1];
       const uint4 packed = make_uint4(pack_f16x2(bf16lo(e0), bf16lo(o0)), pack_f16x2(bf16hi(e0), bf16hi(o0)),
                                       pack_f16x2(bf16lo(e1), bf16lo(o1)), pack_f16x2(bf16hi(e1), bf16hi(o1)));
       *reinterpret_cast<uint4*>(v2_s + (tk >> 1) * kHeadDim + part * 8 + (odd ? 4 : 0)) = packed;
@@ -491,8 +492,9 @@ __global__ __launch_bounds__(kThreads, KVP_EVAL_WAVES_PER_SIMD) void attention_k
           for (int e = 0; e < 8; ++e) {
             const float p0 = __builtin_amdgcn_exp2f(fmaf(acc[2 * e], a.scale2, -m_safe));
             const float p1 = __builtin_amdgcn_exp2f(fmaf(acc[2 * e + 1], a.scale2, -m_safe));
-            const half2_t ph = {static_cast<_Float16>(p0), static_cast<_Float16>(p1)};
-            zsum += static_cast<float>(ph[0]) + static_cast<float>(ph[1]);
+            typedef float float2_t __attribute__((ext_vector_type(2)));
+            const half2_t ph = __builtin_convertvector(float2_t{p0, p1}, half2_t);   // round to nearest even
+            zsum = __builtin_amdgcn_fdot2(ph, half2_t{1, 1}, zsum, false);
             p2_s[(acc_row(lane, 2 * e) >> 1) * kRowsPerBlock + rloc] = as_u32(ph);
           }
         } else {
@@ -511,10 +513,15 @@ __global__ __launch_bounds__(kThreads, KVP_EVAL_WAVES_PER_SIMD) void attention_k
         const float4 a0 = *reinterpret_cast<const float4*>(alpha_s + 4 * ty);
         const float4 a1 = *reinterpret_cast<const float4*>(alpha_s + 64 + 4 * ty);
         const float al[8] = {a0.x, a0.y, a0.z, a0.w, a1.x, a1.y, a1.z, a1.w};
+        bool moved = false;
 #pragma unroll
-        for (int i = 0; i < 8; ++i)
+        for (int i = 0; i < 8; ++i) moved |= al[i] != 1.0f;
+        if (__builtin_amdgcn_ballot_w64(moved)) {   // the running maximum of one of this wave's rows moved
 #pragma unroll
-          for (int j = 0; j < 8; ++j) o[8 * i + j] *= al[i];
+          for (int i = 0; i < 8; ++i)
+#pragma unroll
+            for (int j = 0; j < 8; ++j) o[8 * i + j] *= al[i];
+        }
         if constexpr (PV_DOT2) {
 #pragma unroll 4
           for (int tp = 0; tp < kTile / 2; ++tp) {
