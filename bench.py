@@ -409,7 +409,7 @@ def side_measurements(kvp, workloads, torch, dev, K8, V8):
         "quantize_GBs_alg_hip_graph": round(alg1 / t_graph_q / 1e9, 1), "dequantize_GBs_alg_hip_graph": round(alg1 / t_graph_d / 1e9, 1),
         "score_us_rotating": round(t_rot_s * 1e6, 1), "select_us": round(t_sel1 * 1e6, 1), "select_k": k1,
         "note": "launch-bound: one quantize call moves 16.3 MB (2 us at peak); times include the per-call launch path; "
-                "a score call is three launches"}
+                "a score call is two launches"}
     del gq, gd, K1, q1, p1, views, Q1, qviews
     # --- long-context int2 config at its true shape (4 KV heads: 16 KiB pages, outlier channels x16) ---
     c5 = workloads.CONFIGS["long_context_int2"]
