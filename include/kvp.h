@@ -278,21 +278,23 @@ int32_t kvp_utility_table(const double* quality, const double* bytes, int32_t n_
 
 enum { KVP_OP_INSERT = 0, KVP_OP_COMPRESS = 1, KVP_OP_EVICT = 2 };
 typedef struct {
-  int32_t ctx, cfg, tier, op; /* context, its configuration after the operation, the tier it is on after it */
+  int32_t ctx, cfg, tier, op; /* context, its configuration after the operation, the tier it is on after it
+                                 (-1: evicted from the last tier, no longer stored) */
 } kvp_policy_op;
 
 /* Greedy placement (appendix, Policy Optimizer; "Eviction-compression configuration selection
  * module").  Context `incoming` enters tier 0 with its highest-quality configuration (fewest
  * bytes, then lowest index, among equals).  Then every bounded tier, first to last, is brought
  * under its capacity by repeatedly applying the operation with the least utility drop among: re-
- * compressing a cache on the tier to a configuration with fewer bytes, or evicting it unchanged to
- * the next tier (ties: lowest context, compress before evict, lowest configuration).  This is the
- * appendix algorithm's pair of single operations; the wider option set of the selection-module text
- * (any method and ratio combined with a move to any lower tier in one step) is not searched, and a
- * cache is never deleted: eviction moves it one tier down.
+ * compressing a cache on the tier to a configuration with fewer bytes, or evicting it: unchanged to
+ * the next tier, or, from the last tier, out of storage (tier -1 in the operation and in ctx_tier;
+ * a cache that is not stored earns utility 0, so the drop is its current utility).  Ties: lowest
+ * context, compress before evict, lowest configuration.  This is the appendix algorithm's pair of
+ * single operations; the wider option set of the selection-module text (any method and ratio
+ * combined with a move to any lower tier in one step) is not searched.
  * bytes, quality: [n_ctx][n_cfg]; frequency: [n_ctx]; ctx_tier (-1 = not stored) and ctx_cfg:
  * [n_ctx], updated in place.  The operations are written to ops (at most max_ops) and counted in
- * *n_ops.  KVP_ERR_SHAPE if the last tier is bounded and cannot be made to fit;
+ * *n_ops.  Every bounded tier fits on return.
  * KVP_ERR_WORKSPACE if max_ops is too small (the state then reflects the operations written). */
 int32_t kvp_policy_insert(int32_t n_ctx, int32_t n_cfg, const double* bytes, const double* quality,
                           const double* frequency, const kvp_tier* tiers, int32_t n_tiers, double alpha,

@@ -12,11 +12,13 @@ Readings (the paper leaves them open):
   * An incoming cache enters the first tier with its highest-quality configuration (fewest bytes,
     then lowest index, among equals).
   * While a tier is over capacity, the operation with the least utility drop is applied: either
-    re-compress a cache on that tier to a configuration with fewer bytes, or evict it unchanged to
-    the next tier.  Ties: lowest context index, compress before evict, lowest configuration index.
+    re-compress a cache on that tier to a configuration with fewer bytes, or evict it: unchanged to
+    the next tier, or, from the last tier, out of storage (the appendix's evict sets the stored ratio
+    to 0; a cache that is not stored has utility 0; tier -1).  Ties: lowest context index, compress
+    before evict, lowest configuration index.
   * Tiers are settled from the first to the last; a negative capacity means unbounded.
 Parity status: pinned by the paper's printed utility examples and its two-context figure
-(tests/golden/policy_examples.txt).
+(tests/golden/policy_examples.txt), plus hand-worked cascades for the tie order and the last-tier eviction.
 """
 from __future__ import annotations
 
@@ -71,16 +73,20 @@ def insert(nbytes, quality, frequency, tiers, alpha, ctx_tier, ctx_cfg, incoming
                         if choice is None or drop < choice[0]:
                             choice = (drop, j, COMPRESS, c)
                 if d + 1 < len(tiers):
-                    drop = u_now - utility(alpha, quality[j][cur], ttft(nbytes[j][cur], tiers[d + 1][1]), frequency[j])
-                    if choice is None or drop < choice[0]:
-                        choice = (drop, j, EVICT, cur)
+                    u_after = utility(alpha, quality[j][cur], ttft(nbytes[j][cur], tiers[d + 1][1]), frequency[j])
+                else:
+                    u_after = 0.0          # leaves storage
+                drop = u_now - u_after
+                if choice is None or drop < choice[0]:
+                    choice = (drop, j, EVICT, cur)
             if choice is None:
-                raise ValueError("the caches do not fit the last tier")
+                raise ValueError("over capacity with nothing stored")
             _, j, op, c = choice
             if op == COMPRESS:
                 ctx_cfg[j] = c
                 ops.append((j, c, d, COMPRESS))
             else:
-                ctx_tier[j] = d + 1
-                ops.append((j, c, d + 1, EVICT))
+                to = d + 1 if d + 1 < len(tiers) else -1
+                ctx_tier[j] = to
+                ops.append((j, c, to, EVICT))
     return ops

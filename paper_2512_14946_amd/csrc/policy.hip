@@ -5,8 +5,9 @@
 //   Util(config, tier) = (alpha * quality - TTFT) * frequency,  TTFT = bytes / tier bandwidth
 //
 // kvp_policy_insert stores one incoming cache and then, tier by tier, applies the operation with
-// the least utility drop (re-compress on the tier, or evict unchanged to the next tier) until the
-// tier fits, as the paper's greedy loop does.  Occupancy is kept incrementally; the candidate scan
+// the least utility drop (re-compress on the tier, or evict: unchanged to the next tier, or out of
+// storage from the last tier, where the cache's utility becomes 0) until the tier fits, as the paper's
+// greedy loop does.  Occupancy is kept incrementally; the candidate scan
 // is O(contexts x configs) per operation.
 
 #include <vector>
@@ -83,21 +84,26 @@ extern "C" int32_t kvp_policy_insert(int32_t n_ctx, int32_t n_cfg, const double*
             found = true; best_drop = drop; best_j = j; best_c = c; best_op = KVP_OP_COMPRESS;
           }
         }
-        if (has_next) {
-          const double drop = u_now - util_of(alpha, Q(j, cur), B(j, cur), tiers[d + 1].bandwidth_bytes_per_s, frequency[j]);
+        {
+          // evict: to the next tier unchanged, or, from the last tier, out of storage (the appendix's evict sets the
+          // stored ratio to 0: the cache leaves the queue; a cache that is not stored earns no utility)
+          const double u_after =
+              has_next ? util_of(alpha, Q(j, cur), B(j, cur), tiers[d + 1].bandwidth_bytes_per_s, frequency[j]) : 0.0;
+          const double drop = u_now - u_after;
           if (!found || drop < best_drop) {
             found = true; best_drop = drop; best_j = j; best_c = cur; best_op = KVP_OP_EVICT;
           }
         }
       }
-      if (!found) { *n_ops = count; return KVP_ERR_SHAPE; }        // nothing left to shrink on the last tier
+      if (!found) { *n_ops = count; return KVP_ERR_SHAPE; }        // over capacity with no member: negative sizes
       if (count == max_ops) { *n_ops = count; return KVP_ERR_WORKSPACE; }
       if (best_op == KVP_OP_COMPRESS) {
         ctx_cfg[best_j] = best_c;
         ops[count++] = kvp_policy_op{best_j, best_c, d, KVP_OP_COMPRESS};
       } else {
-        ctx_tier[best_j] = d + 1;
-        ops[count++] = kvp_policy_op{best_j, best_c, d + 1, KVP_OP_EVICT};
+        const int32_t to = has_next ? d + 1 : -1;
+        ctx_tier[best_j] = to;
+        ops[count++] = kvp_policy_op{best_j, best_c, to, KVP_OP_EVICT};
         for (size_t i = 0; i < members.size(); ++i)
           if (members[i] == best_j) { members.erase(members.begin() + static_cast<long>(i)); break; }
       }

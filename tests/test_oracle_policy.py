@@ -76,14 +76,16 @@ def test_two_context_figure_arithmetic_and_greedy_outcome():
     assert total == pytest.approx(want["joint"][0]) and mean_q == want["joint"][1]
 
 
-def test_unbounded_first_tier_needs_no_operation_and_overfull_last_tier_is_an_error():
+def test_unbounded_first_tier_needs_no_operation_and_overfull_last_tier_evicts_out_of_storage():
     nbytes, quality, _ = _figure_instance()
     ctx_tier, ctx_cfg = [-1, -1], [0, 0]
     for i in range(2):
         ops = policy.insert(nbytes, quality, [1.0, 1.0], [(-1.0, 20 * GB)], 1.0, ctx_tier, ctx_cfg, i)
         assert len(ops) == 1 and ops[0][3] == policy.INSERT
-    with pytest.raises(ValueError):
-        policy.insert(nbytes, quality, [1.0, 1.0], [(0.1 * GB, 20 * GB)], 1.0, [-1, -1], [0, 0], 0)
+    # a single bounded tier that nothing fits: the cache is compressed as far as that lowers the drop, then leaves
+    ctx_tier, ctx_cfg = [-1, -1], [0, 0]
+    ops = policy.insert(nbytes, quality, [1.0, 1.0], [(0.1 * GB, 20 * GB)], 1.0, ctx_tier, ctx_cfg, 0)
+    assert ops[-1][2] == -1 and ops[-1][3] == policy.EVICT and ctx_tier == [-1, -1]
 
 
 def _golden_ops(kind):
@@ -104,6 +106,18 @@ def test_three_tier_cascade_and_tie_order_worked_by_hand():
     assert u(1.0, 1.0, policy.ttft(4 * GB, 8 * GB), 1.0) - u(1.0, 0.5, policy.ttft(2 * GB, 8 * GB), 1.0) == 0.25
     assert u(1.0, 0.5, policy.ttft(2 * GB, 8 * GB), 1.0) - u(1.0, 0.5, policy.ttft(2 * GB, 4 * GB), 1.0) == 0.25
     assert u(1.0, 1.0, policy.ttft(2 * GB, 4 * GB), 1.0) - u(1.0, 1.0, policy.ttft(2 * GB, 1 * GB), 1.0) == 1.5
+
+
+def test_eviction_from_the_last_tier_worked_by_hand():
+    nbytes, quality = [[2 * GB, 1 * GB], [4 * GB, 2 * GB]], [[1.0, 0.5], [1.0, 0.5]]
+    ctx_tier, ctx_cfg = [0, -1], [0, 0]
+    ops = policy.insert(nbytes, quality, [2.0, 1.0], [(2 * GB, 4 * GB)], 1.0, ctx_tier, ctx_cfg, 1)
+    assert ops == _golden_ops("last_tier_evict")
+    assert ctx_tier == [0, -1] and ctx_cfg == [0, 1]
+    u = policy.utility                                  # the drops of the derivation, from the utility function alone
+    assert u(1.0, 1.0, policy.ttft(2 * GB, 4 * GB), 2.0) == 1.0
+    assert u(1.0, 1.0, policy.ttft(2 * GB, 4 * GB), 2.0) - u(1.0, 0.5, policy.ttft(1 * GB, 4 * GB), 2.0) == 0.5
+    assert u(1.0, 1.0, policy.ttft(4 * GB, 4 * GB), 1.0) == 0.0 and u(1.0, 0.5, policy.ttft(2 * GB, 4 * GB), 1.0) == 0.0
 
 
 def test_equal_drops_inside_one_context_compress_first_lowest_configuration():

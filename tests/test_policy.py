@@ -62,6 +62,14 @@ def test_hand_worked_three_tier_cascade_and_tie_order(kvp):
     assert got == _golden_ops("one_context_tie")
 
 
+def test_hand_worked_eviction_from_the_last_tier(kvp):
+    ctx_tier, ctx_cfg = np.array([0, -1], np.int32), np.array([0, 0], np.int32)
+    got = kvp.kvp_policy_insert([[2 * GB, 1 * GB], [4 * GB, 2 * GB]], [[1.0, 0.5], [1.0, 0.5]], [2.0, 1.0],
+                                [(2 * GB, 4 * GB)], 1.0, ctx_tier, ctx_cfg, 1)
+    assert got == _golden_ops("last_tier_evict")
+    assert ctx_tier.tolist() == [0, -1] and ctx_cfg.tolist() == [0, 1]
+
+
 @pytest.mark.parametrize("seed", range(20))
 def test_random_instances_match_oracle(kvp, seed):
     rng = np.random.default_rng(seed)
@@ -75,7 +83,8 @@ def test_random_instances_match_oracle(kvp, seed):
         quality = np.round(quality, 1)                    # many ties
     freq = rng.integers(1, 5, n_ctx).astype(float)
     tiers = [(float(rng.uniform(2, 12)) * GB, 20 * GB / 10 ** d) for d in range(n_tiers)]
-    tiers[-1] = (-1.0, tiers[-1][1])
+    if seed % 2 == 0:
+        tiers[-1] = (-1.0, tiers[-1][1])                  # odd seeds keep a bounded last tier: caches may leave storage
     alpha = float(rng.choice([0.1, 0.5, 1.0, 3.0]))
     t_lib, c_lib = np.full(n_ctx, -1, np.int32), np.zeros(n_ctx, np.int32)
     t_ref, c_ref = [-1] * n_ctx, [0] * n_ctx
@@ -93,8 +102,8 @@ def test_random_instances_match_oracle(kvp, seed):
 def test_errors(kvp):
     nbytes, quality = [[4 * GB]], [[1.0]]
     t, c = np.array([-1], np.int32), np.array([0], np.int32)
-    with pytest.raises(kvp.KVPError):                      # a bounded last tier that cannot fit
-        kvp.kvp_policy_insert(nbytes, quality, [1.0], [(1 * GB, 20 * GB)], 1.0, t, c, 0)
+    got = kvp.kvp_policy_insert(nbytes, quality, [1.0], [(1 * GB, 20 * GB)], 1.0, t, c, 0)
+    assert got[-1][2] == -1 and got[-1][3] == kvp.KVP_OP_EVICT and t[0] == -1   # does not fit the only tier: leaves storage
     with pytest.raises(kvp.KVPError):                      # bandwidth must be positive
         kvp.kvp_utility_table([1.0], [1.0], [(-1, 0.0)], 1.0)
     t, c = np.array([-1, 0], np.int32), np.array([0, 0], np.int32)
