@@ -232,8 +232,8 @@ size_t kvp_eval_workspace_bytes(int64_t L, int64_t Hkv, int64_t Hq, int64_t W, i
  * product of the proxy is formed; logits, softmax statistics and accumulation are fp32 in every mode.
  * 0 (default): vector ALU with 16-bit operands: the probabilities rounded to fp16 (nearest even; the row sums
  *   use the rounded values) and V-hat as fp16, two tokens per v_dot2_f32_f16.  V-hat is a bf16 value and exact in
- *   fp16 for 2^-14 <= |v| <= 65504; smaller magnitudes round to multiples of 2^-24 and larger ones saturate at 65504,
- *   so caches with |V| beyond that range need one of the other modes.  Losses agree with KVP_EVAL_PV_FP32 within
+ *   fp16 for 2^-14 <= |v| <= 65504; smaller magnitudes round to multiples of 2^-24 and larger ones become infinite
+ *   (the losses then come out non-finite), so caches with |V| beyond that range need one of the other modes.  Losses agree with KVP_EVAL_PV_FP32 within
  *   1e-4 relative (3e-5 measured on the 40-configuration sweep).
  * KVP_EVAL_PV_FP32: vector ALU with fp32 probabilities and V-hat, one fma per token and output; 1.2x slower.
  * KVP_EVAL_PV_MATRIX_CORES: on the matrix cores (P as the sum of two bf16 terms, relative error 2^-18); the

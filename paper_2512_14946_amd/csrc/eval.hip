@@ -27,7 +27,8 @@
 // query and 16 keys and the online-softmax statistics stay lane-private.  The P.V product has two
 // implementations, chosen per call:
 //   vector ALU, 16-bit operands (default): token pairs of the probabilities (rounded to fp16, nearest even) and
-//     of V-hat (a bf16 value, exact in fp16 for 2^-14 <= |v| <= 65504) go to LDS as packed halves, and each thread
+//     of V-hat (a bf16 value, exact in fp16 for 2^-14 <= |v| <= 65504; larger magnitudes become infinite and the
+//     loss non-finite) go to LDS as packed halves, and each thread
 //     accumulates an 8x8 tile of the 128x128 output in fp32 with v_dot2_f32_f16, two tokens per instruction (the
 //     matrix cores are kept for the query x key contraction).  The row sums use the rounded probabilities, so every
 //     output stays a convex combination of V-hat rows; rounding P moves the losses by less than 1e-4 relative;
@@ -111,12 +112,11 @@ __device__ __forceinline__ half2_t as_half2(uint32_t u) {
   c.u = u;
   return c.h;
 }
-// two floats that are exact in fp16 (or beyond its range: rounded toward zero, clamped at 65504) as packed halves
+// two floats as packed halves, round to nearest even: exact for values fp16 holds, infinite beyond 65504 (so an
+// out-of-range V-hat surfaces as a non-finite loss instead of a plausible wrong one)
 __device__ __forceinline__ uint32_t pack_f16x2(float lo, float hi) {
-  typedef __fp16 fp16x2 __attribute__((ext_vector_type(2)));
-  union { fp16x2 h; uint32_t u; } c;
-  c.h = __builtin_amdgcn_cvt_pkrtz(lo, hi);
-  return c.u;
+  typedef float float2_t __attribute__((ext_vector_type(2)));
+  return as_u32(__builtin_convertvector(float2_t{lo, hi}, half2_t));
 }
 
 __device__ __forceinline__ int acc_row(int lane, int v) { return (lane >> 5) * 4 + (v >> 2) * 8 + (v & 3); }

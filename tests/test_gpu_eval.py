@@ -102,6 +102,30 @@ def test_pv_modes_agree():
     assert out["pv_dot2_fp16"][3] == 0.0 and ref[3] == 0.0
 
 
+def test_value_range_of_the_fp16_pair_form():
+    """V beyond the fp16 range: the default P.V form (fp16 pairs) must answer with a non-finite loss, never a
+    plausible number; the fp32 form stays within tolerance of the oracle.  Small magnitudes (fp16 subnormals)
+    stay within tolerance in both."""
+    kvp = _kvp()
+    L, W, G, H, T, D = 1, 32, 2, 1, 160, 128
+    print("[case] eval value range", dict(L=L, W=W, G=G, H=H, T=T), flush=True)
+    K, V = workloads.make_kv(L, T, H, D, seed=11, outlier_scale=8.0)
+    Q = workloads.make_q(L, W, G * H, D, seed=11)
+    cfgs = [(16, 0, T), (8, 32, T), (4, 64, 80)]
+    big = V.clone()
+    big[0, 3, 0, 5] = 1.0e5
+    got = kvp.kvp_eval_configs(Q.to(DEV), K.to(DEV), big.to(DEV), cfgs).cpu().numpy()
+    assert not np.all(np.isfinite(got))
+    ref, _ = oracle.eval_configs(torch_bits(Q), torch_bits(K), torch_bits(big), cfgs)
+    got32 = kvp.kvp_eval_configs(Q.to(DEV), K.to(DEV), big.to(DEV), cfgs, pv_fp32=True).cpu().numpy()
+    assert np.all(np.abs(got32 - ref) <= 1e-2 * np.abs(ref) + 1e-5), (got32, ref)
+    small = (V.float() * 2.0 ** -12).to(torch.bfloat16)          # |v| around 2^-12: many values below 2^-14
+    ref, _ = oracle.eval_configs(torch_bits(Q), torch_bits(K), torch_bits(small), cfgs)
+    for kw in ({}, {"pv_fp32": True}):
+        got = kvp.kvp_eval_configs(Q.to(DEV), K.to(DEV), small.to(DEV), cfgs, **kw).cpu().numpy()
+        assert np.all(np.abs(got - ref) <= 1e-2 * np.abs(ref) + 1e-5), (kw, got, ref)
+
+
 def test_errors():
     kvp = _kvp()
     q = torch.zeros(1, 8, 4, 128, dtype=torch.bfloat16, device=DEV)
