@@ -194,9 +194,11 @@ def _need_cuda(*ts):
 
 
 def _view(t: torch.Tensor) -> _View:
+    # the marshalled struct is cached on the tensor, keyed by everything it is made of (an in-place
+    # transpose_ / as_strided_ / set_ changes shape or strides under the same storage pointer)
     c = getattr(t, "_kvp_view", None)
-    if c is not None and c[0] == t.data_ptr() and c[1] == t.numel():
-        return c[2]
+    if c is not None and c[0] == t.data_ptr() and c[1] == t.shape and c[2] == t.stride():
+        return c[3]
     if t.dtype != torch.bfloat16 or t.dim() != 4:
         raise ValueError("expected a bf16 tensor [L][T][H][D]")
     if t.stride(3) != 1:
@@ -204,7 +206,7 @@ def _view(t: torch.Tensor) -> _View:
     L, T, H, D = t.shape
     v = _View(t.data_ptr(), L, T, H, D, t.stride(0), t.stride(1), t.stride(2))
     try:
-        t._kvp_view = (t.data_ptr(), t.numel(), v)
+        t._kvp_view = (t.data_ptr(), t.shape, t.stride(), v)
     except Exception:   # a tensor type that takes no attributes
         pass
     return v
@@ -212,8 +214,10 @@ def _view(t: torch.Tensor) -> _View:
 
 def _paged(p: PagedKV) -> _Paged:
     c = p.__dict__.get("_c")
-    if c is not None and c[0] is p.pool and c[1] is p.block_table and c[2] == p.T and c[3] == p.pool.data_ptr():
-        return c[4]
+    if (c is not None and c[0] is p.pool and c[1] is p.block_table and c[2] == p.T and c[3] == p.pool.data_ptr()
+            and c[4] == p.pool.shape and c[5] == p.pool.stride() and c[6] == p.block_table.data_ptr()
+            and c[7] == p.block_table.shape):
+        return c[8]
     pool = p.pool
     if pool.dtype != torch.bfloat16 or pool.dim() != 5 or not pool[0].is_contiguous():
         raise ValueError("pool must be bf16 [L][num_blocks][bs][H][D], contiguous per layer")
@@ -224,15 +228,18 @@ def _paged(p: PagedKV) -> _Paged:
         raise ValueError("block_table is shorter than ceil(T / bs)")
     _need_cuda(pool, p.block_table)
     v = _Paged(pool.data_ptr(), p.block_table.data_ptr(), L, NB, bs, H, D, p.T, pool.stride(0))
-    p.__dict__["_c"] = (p.pool, p.block_table, p.T, pool.data_ptr(), v)
+    p.__dict__["_c"] = (p.pool, p.block_table, p.T, pool.data_ptr(), pool.shape, pool.stride(), p.block_table.data_ptr(),
+                        p.block_table.shape, v)
     return v
 
 
 def _qplane(q: QPlane) -> _QPlane:
     c = q.__dict__.get("_c")
     if (c is not None and c[0] is q.codes and c[1] is q.scales and c[2] is q.mins and c[3] == q.T and c[4] == q.bits
-            and c[5] == q.group and c[6] == q.group_axis and c[7] == q.codes.data_ptr()):
-        return c[8]
+            and c[5] == q.group and c[6] == q.group_axis and c[7] == q.codes.data_ptr() and c[8] == q.codes.shape
+            and c[9] == q.scales.data_ptr() and c[10] == q.scales.shape
+            and (q.mins is None or (c[11] == q.mins.data_ptr() and c[12] == q.mins.shape))):
+        return c[13]
     if q.codes.dtype != torch.uint8 or q.scales.dtype != torch.float32:
         raise ValueError("codes must be uint8 and scales float32")
     if not (q.codes.is_contiguous() and q.scales.is_contiguous()):
@@ -249,7 +256,8 @@ def _qplane(q: QPlane) -> _QPlane:
         mins = q.mins.data_ptr()
     _need_cuda(q.codes, q.scales, q.mins)
     v = _QPlane(q.codes.data_ptr(), q.scales.data_ptr(), mins, q.bits, q.group, L, q.T, Tp, H, D, q.group_axis)
-    q.__dict__["_c"] = (q.codes, q.scales, q.mins, q.T, q.bits, q.group, q.group_axis, q.codes.data_ptr(), v)
+    q.__dict__["_c"] = (q.codes, q.scales, q.mins, q.T, q.bits, q.group, q.group_axis, q.codes.data_ptr(), q.codes.shape,
+                        q.scales.data_ptr(), q.scales.shape, mins, None if q.mins is None else q.mins.shape, v)
     return v
 
 
