@@ -45,6 +45,7 @@ constexpr int kWavesA = 8;                         // waves per block, pass A (2
 constexpr int kWavesB = 8;                         // waves per block, pass B
 constexpr int kPitch = 136;                        // bf16 elements per LDS row (272 B)
 constexpr int kMaxRows = 512;                      // G*W limit (16 query tiles)
+constexpr int kFoldChunks = 16;                    // up to this many key chunks pass B combines the chunk statistics itself
 constexpr float kLog2e = 1.4426950408889634f;
 
 struct ScoreArgs {
@@ -89,6 +90,21 @@ __device__ __forceinline__ void load_key_tile(const ScoreArgs& a, const uint16_t
 __device__ __forceinline__ float combined_bias(const ScoreArgs& a, int lh, int r) {
   if (r >= a.M) return INFINITY;
   const float2* part = a.partial + static_cast<int64_t>(lh) * a.n_chunks * a.Mrows + r;
+  if (a.n_chunks <= kFoldChunks) {
+    // all chunk statistics of the row requested at once (one memory latency instead of one per chunk)
+    float2 p[kFoldChunks];
+#pragma unroll
+    for (int c = 0; c < kFoldChunks; ++c)
+      p[c] = c < a.n_chunks ? part[static_cast<int64_t>(c) * a.Mrows] : make_float2(-INFINITY, 0.0f);
+    float m = -INFINITY;
+#pragma unroll
+    for (int c = 0; c < kFoldChunks; ++c) m = fmaxf(m, p[c].x);
+    float z = 0.0f;
+#pragma unroll
+    for (int c = 0; c < kFoldChunks; ++c)
+      if (p[c].x != -INFINITY) z += p[c].y * __builtin_amdgcn_exp2f(p[c].x - m);
+    return m + __builtin_amdgcn_logf(z);  // v_log_f32 is log2
+  }
   float m = -INFINITY;
   for (int c = 0; c < a.n_chunks; ++c) m = fmaxf(m, part[static_cast<int64_t>(c) * a.Mrows].x);
   float z = 0.0f;
@@ -115,16 +131,33 @@ __global__ __launch_bounds__((PASS_B ? kWavesB : kWavesA) * kWave, 2) void score
   const uint16_t* kbase = a.k + static_cast<int64_t>(l) * a.k_sl + static_cast<int64_t>(h) * a.k_sh;
   const int win0 = a.T - a.W;  // first window position
 
-  // ---- stage the window queries of this (layer, kv head): row r = u * W + w, zeros beyond M ----
-  for (int idx = threadIdx.x; idx < a.Mrows * 16; idx += kThreads) {
-    const int r = idx >> 4, part = idx & 15;
-    uint4 v = make_uint4(0, 0, 0, 0);
-    if (r < a.M) {
-      const int u = r / a.W, w = r - u * a.W;
-      v = *reinterpret_cast<const uint4*>(a.q + static_cast<int64_t>(l) * a.q_sl + static_cast<int64_t>(w) * a.q_st +
-                                          static_cast<int64_t>(h * a.G + u) * a.q_sh + part * 8);
+  // this wave's first key tile is requested before anything else, so that its latency overlaps the prologue
+  constexpr int kTileStride = 32 * kWavesPerBlock;
+  const int t_begin = chunk * a.chunk_keys + wave * 32;
+  const int t_end = min(a.T, (chunk + 1) * a.chunk_keys);   // chunk_keys is a multiple of kTileStride
+  uint4 kop[8];
+  if (t_begin < t_end) load_key_tile(a, kbase, t_begin, lane, kop);
+
+  // ---- stage the window queries of this (layer, kv head): row r = u * W + w, zeros beyond M.  A thread's
+  //      (at most NQT) pieces are all requested before the first one is stored ----
+  {
+    uint4 piece[NQT];
+#pragma unroll
+    for (int i = 0; i < NQT; ++i) {
+      const int idx = static_cast<int>(threadIdx.x) + i * kThreads;
+      const int r = idx >> 4, part = idx & 15;
+      piece[i] = make_uint4(0, 0, 0, 0);
+      if (r < a.M) {
+        const int u = r / a.W, w = r - u * a.W;
+        piece[i] = *reinterpret_cast<const uint4*>(a.q + static_cast<int64_t>(l) * a.q_sl + static_cast<int64_t>(w) * a.q_st +
+                                                   static_cast<int64_t>(h * a.G + u) * a.q_sh + part * 8);
+      }
     }
-    *reinterpret_cast<uint4*>(q_s + r * kPitch + part * 8) = v;
+#pragma unroll
+    for (int i = 0; i < NQT; ++i) {
+      const int idx = static_cast<int>(threadIdx.x) + i * kThreads;
+      if (idx < a.Mrows * 16) *reinterpret_cast<uint4*>(q_s + (idx >> 4) * kPitch + (idx & 15) * 8) = piece[i];
+    }
   }
   for (int r = threadIdx.x; r < a.Mrows; r += kThreads) {
     wpos_s[r] = r % a.W;
@@ -273,12 +306,8 @@ __global__ __launch_bounds__((PASS_B ? kWavesB : kWavesA) * kWave, 2) void score
 
   // ---- this wave's key tiles: every kWavesPerBlock-th tile of the chunk, so that the few masked tiles at the
   //      end of a row (each costs more) are spread over the waves instead of all landing on the last one ----
-  constexpr int kTileStride = 32 * kWavesPerBlock;
-  const int t_begin = chunk * a.chunk_keys + wave * 32;
-  const int t_end = min(a.T, (chunk + 1) * a.chunk_keys);   // chunk_keys is a multiple of kTileStride
   if (t_begin < t_end) {
-    uint4 kop[8], knext[8];
-    load_key_tile(a, kbase, t_begin, lane, kop);
+    uint4 knext[8];
     for (int tk0 = t_begin; tk0 < t_end; tk0 += kTileStride) {
       const bool more = tk0 + kTileStride < t_end;
       if (more) load_key_tile(a, kbase, tk0 + kTileStride, lane, knext);
@@ -409,7 +438,7 @@ int32_t score_tokens_impl(const kvp_view* q_win, const kvp_view* k, int32_t caus
   const dim3 grid(static_cast<unsigned>(p.n_chunks), static_cast<unsigned>(L * Hkv));
   // With few chunks every pass-B block combines the chunk statistics of its (layer, head) itself (a few KiB of
   // reads from the cache): a call is two launches, which is what counts for small, launch-bound shapes.
-  a.fold_combine = p.n_chunks <= 16 ? 1 : 0;
+  a.fold_combine = p.n_chunks <= kFoldChunks ? 1 : 0;
   launch_pass_a<1>(p.nqt, grid, st, a);
   if (!a.fold_combine) combine_kernel<<<dim3(static_cast<unsigned>(L * Hkv)), 256, 0, st>>>(a);
   launch_pass_b(p.nqt, grid, st, a);
