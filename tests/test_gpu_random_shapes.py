@@ -139,8 +139,9 @@ def test_gather_quantize_and_scatter_restore_random(seed):
 
 
 @pytest.mark.parametrize("seed", range(5))
-@pytest.mark.parametrize("pv_matrix_cores", [False, True], ids=["pv_vector_alu", "pv_matrix_cores"])
-def test_eval_configs_random(seed, pv_matrix_cores):
+@pytest.mark.parametrize("pv", ["pv_dot2_fp16", "pv_fp32", "pv_matrix_cores"])
+def test_eval_configs_random(seed, pv):
+    pv_kw = {"pv_dot2_fp16": {}, "pv_fp32": {"pv_fp32": True}, "pv_matrix_cores": {"pv_matrix_cores": True}}[pv]
     kvp = _kvp()
     rng, L, H, T, G, W = _shape(seed + 100)
     T = min(max(T, 2), 600)                                   # the oracle is O(configs x rows x T x D)
@@ -155,10 +156,10 @@ def test_eval_configs_random(seed, pv_matrix_cores):
     # at most 8 distinct keep levels
     levels = sorted({c[2] for c in cfgs})[:8]
     cfgs = [c for c in cfgs if c[2] in levels]
-    print("[case] random eval", dict(seed=seed, L=L, H=H, T=T, G=G, W=W, cfgs=cfgs, pv_matrix_cores=pv_matrix_cores), flush=True)
+    print("[case] random eval", dict(seed=seed, L=L, H=H, T=T, G=G, W=W, cfgs=cfgs, pv=pv), flush=True)
     K, V = workloads.make_kv(L, T, H, D, seed=seed)
     Q = workloads.make_q(L, W, G * H, D, seed=seed)
-    loss = kvp.kvp_eval_configs(Q.to(DEV), K.to(DEV), V.to(DEV), cfgs, pv_matrix_cores=pv_matrix_cores)
+    loss = kvp.kvp_eval_configs(Q.to(DEV), K.to(DEV), V.to(DEV), cfgs, **pv_kw)
     torch.cuda.synchronize()
     ref, _ = oracle.eval_configs(torch_bits(Q), torch_bits(K), torch_bits(V), cfgs)
     loss = loss.cpu().numpy()
