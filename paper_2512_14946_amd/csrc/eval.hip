@@ -291,6 +291,7 @@ __global__ __launch_bounds__(kThreads, KVP_EVAL_WAVES_PER_SIMD) void attention_k
   __shared__ __attribute__((aligned(16))) float alpha_s[PV_MFMA ? 4 : kRowsPerBlock];
   __shared__ __attribute__((aligned(16))) float z_s[PV_MFMA ? 4 : kRowsPerBlock];
   __shared__ int tok_s[kTile];
+  __shared__ int mask_s[2];   // per tile parity: some slot of the tile needs the causal / padding mask
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int half = lane >> 5;
@@ -398,14 +399,18 @@ __global__ __launch_bounds__(kThreads, KVP_EVAL_WAVES_PER_SIMD) void attention_k
   uint4 k_b = load_row(kbase, a.k_st, t_b), v_b = load_row(vbase, a.v_st, t_b);
   int tn_a = load_token(nxt, tk_a), tn_b = load_token(nxt, tk_b);
 
+  if (tid == 0) mask_s[0] = mask_s[1] = 0;
+  int parity = 0;
   while (cur.seg < n_seg) {
     const int seg = cur.seg;
     {
       __syncthreads();  // the previous tile's LDS is no longer read
+      if (tid == 0) mask_s[parity ^ 1] = 0;   // the previous tile's flag has been read by everybody
       // ---- stage 32 tokens: K-hat and V-hat (the dequantized values are bf16 values) ----
       has_window = false;
       stage(tk_a, t_a, k_a, v_a);
       stage(tk_b, t_b, k_b, v_b);
+      if (has_window) mask_s[parity] = 1;     // rare; every writer stores the same value
       // ---- run ahead: rows of the next tile, permutation entries of the one after ----
       const Cursor nn = advance(nxt);
       t_a = tn_a;
@@ -418,7 +423,9 @@ __global__ __launch_bounds__(kThreads, KVP_EVAL_WAVES_PER_SIMD) void attention_k
       tn_b = load_token(nn, tk_b);
       cur = nxt;
       nxt = nn;
-      const bool need_mask = __syncthreads_or(has_window ? 1 : 0) != 0;  // also publishes the stage
+      __syncthreads();                         // publishes the stage and the flag
+      const bool need_mask = mask_s[parity] != 0;
+      parity ^= 1;
 
       // ---- logits of 32 keys x this wave's 32 queries, online softmax ----
       floatx16 acc = {0};
