@@ -437,7 +437,7 @@ def side_measurements(kvp, workloads, torch, dev, K8, V8):
     k5 = kvp.kvp_keep_count(c5["keep_ratio"], c5["T"])
     idx5 = torch.empty(rows5, k5, dtype=torch.int32, device=dev)
     wsel5 = torch.empty(kvp.kvp_select_workspace_bytes(rows5, c5["T"], k5), dtype=torch.uint8, device=dev)
-    t5sel = _time_loop(torch, lambda: kvp.kvp_select_topk(sc5.view(rows5, c5["T"]), k5, idx5, ws=wsel5), 10)
+    t5sel = _time_loop(torch, lambda: kvp.kvp_select_topk(sc5.view(rows5, c5["T"]), k5, idx5, ws=wsel5), 100, warm=20)
     M5 = c5["G"] * c5["W"]
     flops5 = 2 * 2.0 * rows5 * M5 * c5["T"] * c5["D"]
     ops["long_context_score_select"] = {
@@ -473,9 +473,10 @@ def side_measurements(kvp, workloads, torch, dev, K8, V8):
     idx = torch.empty(Ls * c["H"], k, dtype=torch.int32, device=dev)
     qk = kvp.alloc_qplane(Ls, k, c["H"], c["D"], c["bits"], c["group"], dev)
     t_score = _time_loop(torch, lambda: kvp.kvp_score_tokens(Qc, Kc, sc, ws=ws), 5)
-    t_sel = _time_loop(torch, lambda: kvp.kvp_select_topk(sc.view(Ls * c["H"], c["T"]), k, idx), 10)
+    sv = sc.view(Ls * c["H"], c["T"])
+    t_sel = _time_loop(torch, lambda: kvp.kvp_select_topk(sv, k, idx), 100, warm=20)   # tens of us per call: long batches
     sm = torch.empty(Ls * c["H"], c["T"], dtype=torch.float32, device=dev)
-    t_smooth = _time_loop(torch, lambda: kvp.kvp_smooth_scores(sc.view(Ls * c["H"], c["T"]), c["W"], 7, "max", out=sm), 10)
+    t_smooth = _time_loop(torch, lambda: kvp.kvp_smooth_scores(sv, c["W"], 7, "max", out=sm), 100, warm=20)
     keep = idx.view(Ls, c["H"], k)
     t_gq = _time_loop(torch, lambda: kvp.kvp_quantize(Kc, qk, keep_idx=keep), 5)
     # restore of the dropped+quantized plane: compact (k-slot pool) and at the original positions (T-token pool)
@@ -510,7 +511,7 @@ def side_measurements(kvp, workloads, torch, dev, K8, V8):
     s = workloads.make_scores(rows, c["T"], seed=0, device=dev)
     idx = torch.empty(rows, k, dtype=torch.int32, device=dev)
     wsel = torch.empty(kvp.kvp_select_workspace_bytes(rows, c["T"], k), dtype=torch.uint8, device=dev)
-    t_sel = _time_loop(torch, lambda: kvp.kvp_select_topk(s, k, idx, ws=wsel), 10)
+    t_sel = _time_loop(torch, lambda: kvp.kvp_select_topk(s, k, idx, ws=wsel), 100, warm=20)
     ops["long_context_select"] = {"workload": f"{rows} rows x {c['T']} squared-normal stand-in scores, k={k}",
                                   "select_us": round(t_sel * 1e6, 1),
                                   "select_GBs_alg": round(rows * (c["T"] + k) * 4 / t_sel / 1e9, 1)}
