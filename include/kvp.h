@@ -309,10 +309,19 @@ int64_t kvp_keep_count(double ratio, int64_t T);
  * and the hardware-counter calibration compare the streaming kernels with. */
 int32_t kvp_copy_bytes(void* dst, const void* src, size_t nbytes, void* stream);
 
+/* Self-test of an arithmetic identity of this build: the asymmetric quantizer forms fl32(1 / scale) as the
+ * hardware reciprocal estimate plus one fma correction step instead of a division.  The call compares that with
+ * the IEEE quotient 1.0f / s for every binary32 s in [2^-60, 2^61) (2^23 significands x 121 exponents, about
+ * 0.3 s of GPU time) and ADDS the number of operands that differ to *mismatches (device memory, 8-byte aligned,
+ * cleared by the caller).  0 on gfx950; a GPU test asserts it, so a part or a compiler that rounds differently
+ * is noticed before any code depends on it. */
+int32_t kvp_selftest_reciprocal(uint64_t* mismatches, void* stream);
+
 const char* kvp_strerror(int32_t code);
 /* 0x00MMmmpp.  1.3: kvp_qplane carries mins and group_axis; scatter restore, score smoothing and
  * kvp_eval_configs_ex exist.  1.4: kvp_select_topk uses its workspace for long rows; kvp_dims,
- * kvp_workspace_bytes and kvp_score_tokens_static exist. */
+ * kvp_workspace_bytes and kvp_score_tokens_static exist.  1.5: KVP_EVAL_PV_FP32, tier -1 in kvp_policy_op,
+ * kvp_selftest_reciprocal. */
 uint32_t kvp_version(void);
 
 #ifdef __cplusplus

@@ -5,7 +5,7 @@ package only marshals torch tensors into that ABI.  There is no CPU fallback: if
 not built, importing the binding raises.
 """
 from .kvp import (  # noqa: F401
-    KVPError, PagedKV, QPlane, alloc_paged, alloc_qplane, kvp_copy_bytes, kvp_dequantize_paged,
+    KVPError, PagedKV, QPlane, alloc_paged, alloc_qplane, kvp_copy_bytes, kvp_selftest_reciprocal, kvp_dequantize_paged,
     kvp_dequantize_paged_scatter,
     kvp_eval_configs, kvp_eval_workspace_bytes, kvp_keep_count, kvp_quantize, kvp_score_tokens,
     kvp_score_tokens_static, KVP_SCORE_STATIC_SCRATCH_BYTES,

@@ -218,7 +218,7 @@ extern "C" const char* kvp_strerror(int32_t code) {
 }
 
 // major.minor.patch as 0x00MMmmpp; the minor number moves whenever the ABI gains a field or an entry point
-extern "C" uint32_t kvp_version(void) { return 0x00010400u; }
+extern "C" uint32_t kvp_version(void) { return 0x00010500u; }
 
 extern "C" size_t kvp_workspace_bytes(int32_t op, const kvp_dims* d) {
   if (!d) return 0;

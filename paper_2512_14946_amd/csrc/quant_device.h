@@ -41,6 +41,15 @@ __device__ __forceinline__ float scale_of_bf16_amax(float amax) {
   return fmaf(r, kC, q0);
 }
 
+// fl32(1 / s) for 2^-60 <= s <= 2^60 without the division sequence: v_rcp_f32 (1 ulp) and one fma correction
+// step.  On gfx950 the result equals the IEEE quotient 1.0f / s for EVERY binary32 s in that range:
+// kvp_selftest_reciprocal runs the comparison over all 2^23 significands x 121 exponents on the device (0.3 s)
+// and a GPU test asserts that it finds no mismatch.
+__device__ __forceinline__ float reciprocal_in_range(float s) {
+  const float y0 = __builtin_amdgcn_rcpf(s);
+  return fmaf(fmaf(-s, y0, 1.0f), y0, y0);
+}
+
 // Group quantizer for QMAX in {7, 127}: scale and the codes (as integral floats) of one lane's
 // 8 elements, bit-exact with rint(fl32(x / scale)), without a division per element and without a
 // branch:
@@ -89,8 +98,8 @@ struct GroupQuantizer {
 
 // Asymmetric codec: codes 0 .. LEVELS of d = fl32(x - mn) on the scale fl32(fl32(mx - mn) / LEVELS).
 // The same remainder-correction step as GroupQuantizer, applied to d; the scale is an arbitrary
-// binary32 value here, so its reciprocal comes from one IEEE division per lane (correctly rounded by
-// definition), which is all the correction step needs to return the correctly rounded quotient.
+// binary32 value here, so the step needs the correctly rounded reciprocal fl32(1 / scale): that is what
+// reciprocal_in_range returns for every operand of its range on this hardware (checked exhaustively on the device).
 template <int LEVELS>
 struct AsymQuantizer {
   float scale, inv, mn;
@@ -110,7 +119,9 @@ struct AsymQuantizer {
       if (unsafe) scale = range / kLevels;
     }
     unsafe = unsafe && scale != 0.0f;
-    inv = (scale == 0.0f) ? 0.0f : 1.0f / scale;
+    // inside the exponent range the corrected hardware reciprocal is the IEEE one (see reciprocal_in_range);
+    // outside it codes8 divides and inv is not used
+    inv = (scale == 0.0f) ? 0.0f : reciprocal_in_range(scale);
   }
   // from parameters computed elsewhere (the same scale, reciprocal and minimum)
   __device__ __forceinline__ AsymQuantizer(float s, float i, float m) : scale(s), inv(i), mn(m) {

@@ -227,3 +227,29 @@ extern "C" int32_t kvp_quantize(const kvp_view* src, const kvp_paged* src_paged,
   }
   return launch_status();
 }
+
+// ---- self-test of the arithmetic identity the asymmetric quantizer leans on ----
+namespace kvp {
+namespace {
+// one thread per significand; every exponent of the range in turn
+__global__ __launch_bounds__(256) void reciprocal_selftest_kernel(unsigned long long* mismatches) {
+  const uint32_t sig = blockIdx.x * 256u + threadIdx.x;   // 0 .. 2^23 - 1
+  uint32_t bad = 0;
+  for (uint32_t e = 127 - 60; e <= 127 + 60; ++e) {
+    const float s = __uint_as_float((e << 23) | sig);
+    if (__float_as_uint(reciprocal_in_range(s)) != __float_as_uint(1.0f / s)) ++bad;
+  }
+  if (bad != 0) atomicAdd(mismatches, static_cast<unsigned long long>(bad));
+}
+}  // namespace
+}  // namespace kvp
+
+extern "C" int32_t kvp_selftest_reciprocal(uint64_t* mismatches, void* stream) {
+  using namespace kvp;
+  if (!mismatches) return KVP_ERR_NULL;
+  if (reinterpret_cast<uintptr_t>(mismatches) & 7u) return KVP_ERR_ALIGN;
+  reciprocal_selftest_kernel<<<dim3((1u << 23) / 256u), 256, 0, as_stream(stream)>>>(
+      reinterpret_cast<unsigned long long*>(mismatches));
+  return launch_status();
+}
+

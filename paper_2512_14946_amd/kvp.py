@@ -109,6 +109,8 @@ def _load(path: str = _LIB_PATH):
     lib.kvp_copy_bytes.argtypes = [_vp, _vp, _sz, _vp]
     lib.kvp_strerror.restype = ctypes.c_char_p
     lib.kvp_strerror.argtypes = [_i32]
+    lib.kvp_selftest_reciprocal.restype = _i32
+    lib.kvp_selftest_reciprocal.argtypes = [_vp, _vp]
     lib.kvp_version.restype = ctypes.c_uint32
     lib.kvp_version.argtypes = []
     return lib
@@ -285,6 +287,13 @@ def _workspace(ws, nbytes: int, device, stream=None):
 
 def kvp_strerror(code: int) -> str:
     return _lib.kvp_strerror(int(code)).decode()
+
+
+def kvp_selftest_reciprocal(stream=None) -> int:
+    """Operands (of 2^23 x 121) for which the corrected hardware reciprocal differs from the IEEE quotient."""
+    out = torch.zeros(1, dtype=torch.int64, device="cuda")
+    _check(_lib.kvp_selftest_reciprocal(out.data_ptr(), _stream(stream)), "kvp_selftest_reciprocal")
+    return int(out.item())
 
 
 def kvp_version() -> int:

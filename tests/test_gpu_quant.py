@@ -333,3 +333,11 @@ def test_hip_graph_replays_match_eager():
         assert torch.equal(got_pool.view(torch.int16), pg.pool.view(torch.int16)), rep
     oc, _ = oracle.quantize(torch_bits(V), 4, 64, Tp=qp.Tp)
     assert np.array_equal(qp.codes.cpu().numpy(), oc)
+
+
+def test_corrected_hardware_reciprocal_equals_ieee_division_on_this_device():
+    # the asymmetric quantizer forms fl32(1 / scale) without a division; the library re-proves on the running GPU
+    # that this equals the IEEE quotient for every operand of the range it is used in (2^23 significands x 121 exponents)
+    kvp = _kvp()
+    _say("reciprocal self-test")
+    assert kvp.kvp_selftest_reciprocal() == 0
